@@ -1,0 +1,225 @@
+"""Pins for the oracle's layer-level functions: the paper's equivalences (Eq. 1, 3, 4 and the
+hybrid cut) by brute force, finite-difference gradients, and a PyTorch-CPU autograd composition
+of library routines as an independent third opinion."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import domino_oracle as O
+from paper_2409_15241_amd import synth
+
+TINY = synth.WORKLOADS["tiny"].replace(seq=16, batch=4)
+TINYL = synth.WORKLOADS["tiny-llama"].replace(seq=16, batch=4)
+
+
+def small(cfg, **kw):
+    """A shrunken config so that fp64 loops stay instant: h=32, 4 heads (d=8), t=2."""
+    base = dict(hidden=32, heads=4, tp=2, ffn=(128 if cfg.arch == 0 else 96), seq=10, batch=4)
+    base.update(kw)
+    return cfg.replace(**base)
+
+
+def setup(cfg, random_affine=True):
+    shards = [{k: (None if v is None else v.astype(np.float64))
+               for k, v in synth.make_rank_params(cfg, r, random_affine=random_affine, std=0.2).items()}
+              for r in range(cfg.tp)]
+    x, dy = synth.make_activations(cfg)
+    return shards, x.astype(np.float64), dy.astype(np.float64)
+
+
+def rel(a, b):
+    return np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300)
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+def test_shard_and_full_are_inverse(base):
+    cfg = small(base)
+    shards, _, _ = setup(cfg)
+    full = O.full_from_shards(shards, cfg)
+    assert full["w_qkv"].shape == (cfg.hidden, 3 * cfg.hidden)
+    assert full["w_down"].shape == (cfg.ffn, cfg.hidden)
+    for r in range(cfg.tp):
+        back = O.shard_params(full, cfg, r)
+        for k, v in shards[r].items():
+            if v is None:
+                assert back[k] is None
+            else:
+                np.testing.assert_array_equal(back[k], v)
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+def test_tp_sharding_reproduces_full_layer(base):
+    """Eq. 1 / Sec. 3.1: sum over ranks of the partials = the unsharded sub-layer output; with the
+    true 'others' every rank's y is the full layer's y; input-gradient partials sum to the full
+    input gradient; each rank's weight gradient is the matching block of the full one."""
+    cfg = small(base)
+    shards, x, dy = setup(cfg)
+    full = O.full_from_shards(shards, cfg)
+    F = O.full_layer_fwd(cfg, full, x)
+    B = O.full_layer_bwd(cfg, full, F, dy)
+    fwd, bwd = O.simulate_tp(cfg, shards, x, dy)
+    assert rel(sum(f["attn_partial"] for f in fwd), F["attn_partial"]) < 1e-12
+    assert rel(sum(f["mlp_partial"] for f in fwd), F["mlp_partial"]) < 1e-12
+    for r in range(cfg.tp):
+        assert rel(fwd[r]["y"], F["y"]) < 1e-12
+        assert rel(bwd[r]["dx"], B["dx"]) < 1e-12
+    assert rel(sum(o["dln2_partial"] for o in bwd), B["dln2_partial"]) < 1e-12
+    assert rel(sum(o["dln1_partial"] for o in bwd), B["dln1_partial"]) < 1e-12
+    for r in range(cfg.tp):
+        want = O.shard_params(B["grads"], cfg, r)
+        for k, v in bwd[r]["grads"].items():
+            if v is None:
+                assert want[k] is None
+            else:
+                assert rel(v, want[k]) < 1e-11, k
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (4, 2), (2, 4), (4, 4)])
+def test_domino_grid_equals_unsliced_rank_layer(base, p, q):
+    """Eq. 3 (rows), Eq. 4 (columns) and their combination (Sec. 3.4), forward and backward."""
+    cfg = small(base, p=p, q=q)
+    shards, x, dy = setup(cfg)
+    oth = {k: v.astype(np.float64) for k, v in synth.make_others(cfg).items()}
+    for r in (0, 1):
+        P = shards[r]
+        F = O.rank_layer_fwd(cfg, P, x, oth["attn_others"], oth["mlp_others"])
+        B = O.rank_layer_bwd(cfg, P, F, dy, oth["dln2_others"], oth["dln1_others"])
+        Fd = O.domino_layer_fwd(cfg, P, x, oth["attn_others"], oth["mlp_others"])
+        Bd = O.domino_layer_bwd(cfg, P, Fd, dy, oth["dln2_others"], oth["dln1_others"])
+        for k in ("attn_partial", "mlp_partial", "y", "x1", "ctx", "lse"):
+            assert rel(Fd[k], F[k]) < 1e-12, k
+        for k in ("dx", "dln2_partial", "dln1_partial"):
+            assert rel(Bd[k], B[k]) < 1e-12, k
+        for k, v in B["grads"].items():
+            if v is not None:
+                assert rel(Bd["grads"][k], v) < 1e-11, k
+
+
+def test_indivisible_cuts_are_rejected():
+    cfg = small(TINY, p=3)
+    shards, x, dy = setup(cfg)
+    with pytest.raises(ValueError):
+        O.domino_layer_fwd(cfg, shards[0], x)
+    with pytest.raises(ValueError):
+        O.domino_layer_fwd(small(TINY, q=3), shards[0], x)
+
+
+def _loss(cfg, P, x, dy, oth):
+    return float((O.rank_layer_fwd(cfg, P, x, oth["attn_others"], oth["mlp_others"])["y"] * dy).sum())
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+@pytest.mark.parametrize("tanh", [1, 0])
+def test_backward_by_central_finite_differences(base, tanh):
+    """Directional derivative of L = sum(y * dy) along a random direction, for x and each
+    parameter tensor of a rank shard (constant 'others', so the rank layer is a closed function)."""
+    if base.arch == 1 and tanh == 0:
+        pytest.skip("GeLU flavour does not apply to SwiGLU")
+    cfg = small(base, gelu_tanh=tanh)
+    shards, x, dy = setup(cfg)
+    oth = {k: v.astype(np.float64) for k, v in synth.make_others(cfg).items()}
+    P = shards[1]
+    F = O.rank_layer_fwd(cfg, P, x, oth["attn_others"], oth["mlp_others"])
+    B = O.rank_layer_bwd(cfg, P, F, dy)          # no incoming 'others' gradients: pure function
+    rng = np.random.default_rng(3)
+    eps = 1e-6
+    v = rng.standard_normal(x.shape)
+    num = (_loss(cfg, P, x + eps * v, dy, oth) - _loss(cfg, P, x - eps * v, dy, oth)) / (2 * eps)
+    assert abs(num - (B["dx"] * v).sum()) <= 1e-6 * max(1.0, abs(num)), "dx"
+    for k, g in B["grads"].items():
+        if g is None:
+            continue
+        v = rng.standard_normal(P[k].shape)
+        Pp, Pm = dict(P), dict(P)
+        Pp[k], Pm[k] = P[k] + eps * v, P[k] - eps * v
+        num = (_loss(cfg, Pp, x, dy, oth) - _loss(cfg, Pm, x, dy, oth)) / (2 * eps)
+        assert abs(num - (g * v).sum()) <= 1e-6 * max(1.0, abs(num)), k
+
+
+def test_incoming_others_gradients_enter_through_the_norms():
+    """dln*_others are added to the partial before the norm's backward: check linearity against
+    the norm backward evaluated separately."""
+    cfg = small(TINY)
+    shards, x, dy = setup(cfg)
+    oth = {k: v.astype(np.float64) for k, v in synth.make_others(cfg).items()}
+    P = shards[0]
+    F = O.rank_layer_fwd(cfg, P, x)
+    B0 = O.rank_layer_bwd(cfg, P, F, dy)
+    B1 = O.rank_layer_bwd(cfg, P, F, dy, dln1_others=oth["dln1_others"])
+    extra, dg, db = O.norm_bwd(oth["dln1_others"], x, P["norm1_g"], F["mean1"], F["rstd1"], False)
+    assert rel(B1["dx"] - B0["dx"], extra) < 1e-10
+    assert rel(B1["grads"]["norm1_g"] - B0["grads"]["norm1_g"], dg) < 1e-10
+    assert rel(B1["dln1_partial"], B0["dln1_partial"]) == 0
+
+
+# ---------------------------------------------------------------- third opinion: torch autograd
+def _torch_layer(cfg, full, x):
+    """Unsharded block composed from PyTorch CPU library routines in fp64."""
+    h, n = cfg.hidden, cfg.heads
+    d = h // n
+    b, s, _ = x.shape
+    F = torch.nn.functional
+    llama = cfg.arch == 1
+
+    def norm(z, g, bb):
+        if llama:
+            return F.rms_norm(z, (h,), g, cfg.norm_eps)
+        return F.layer_norm(z, (h,), g, bb, cfg.norm_eps)
+
+    ln1 = norm(x, full["norm1_g"], full["norm1_b"])
+    qkv = ln1 @ full["w_qkv"]
+    if not llama:
+        qkv = qkv + full["b_qkv"]
+    q, k, v = (t.reshape(b, s, n, d).transpose(1, 2) for t in qkv.split(h, dim=-1))
+    if llama:
+        inv = cfg.rope_base ** (-torch.arange(0, d, 2, dtype=torch.float64) / d)
+        ang = torch.outer(torch.arange(s, dtype=torch.float64), inv)
+        cos, sin = torch.cat([ang.cos(), ang.cos()], -1), torch.cat([ang.sin(), ang.sin()], -1)
+        rot = lambda z: torch.cat([-z[..., d // 2:], z[..., :d // 2]], -1)
+        q, k = q * cos + rot(q) * sin, k * cos + rot(k) * sin
+    ctx = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(b, s, h)
+    x1 = x + ctx @ full["w_o"]
+    if not llama:
+        x1 = x1 + full["b_o"]
+    ln2 = norm(x1, full["norm2_g"], full["norm2_b"])
+    pre = ln2 @ full["w_up"]
+    if llama:
+        g_, u_ = pre.split(cfg.ffn, dim=-1)
+        act = F.silu(g_) * u_
+    else:
+        act = F.gelu(pre + full["b_up"], approximate="tanh" if cfg.gelu_tanh else "none")
+    y = x1 + act @ full["w_down"]
+    if not llama:
+        y = y + full["b_down"]
+    return y
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+def test_full_layer_matches_torch_autograd_composition(base):
+    cfg = small(base)
+    shards, x, dy = setup(cfg)
+    full = O.full_from_shards(shards, cfg)
+    Fo = O.full_layer_fwd(cfg, full, x)
+    Bo = O.full_layer_bwd(cfg, full, Fo, dy)
+    ft = {k: (None if v is None else torch.tensor(v, requires_grad=True)) for k, v in full.items()}
+    xt = torch.tensor(x, requires_grad=True)
+    yt = _torch_layer(cfg, ft, xt)
+    yt.backward(torch.tensor(dy))
+    assert rel(Fo["y"], yt.detach().numpy()) < 1e-12
+    assert rel(Bo["dx"], xt.grad.numpy()) < 1e-11
+    for k, g in Bo["grads"].items():
+        if g is not None:
+            assert rel(g, ft[k].grad.numpy()) < 1e-11, k
+
+
+def test_algorithmic_flops_match_hand_count():
+    # GPT-3-13B shard: 2*M*(h*3hl + hl*h + h*fl + fl*h) + causal attention, times 3
+    cfg = synth.WORKLOADS["gpt3-13b"]
+    M = 8192
+    want = 3 * (2 * M * (5120 * 1920 + 640 * 5120 + 5120 * 2560 + 2560 * 5120) + 2 * 4 * 5 * 2048 ** 2 * 128)
+    assert O.algorithmic_flops(cfg) == want
+    assert abs(want / 1e9 - 1997.2) < 0.1
+    assert abs(O.algorithmic_flops(synth.WORKLOADS["llama2-13b"]) / 1e9 - 4155.4) < 0.1
