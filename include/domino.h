@@ -1,0 +1,196 @@
+/* domino.h - C ABI of the MI355X-native rank-local hot path of Domino tensor-parallel training.
+ *
+ * One tensor-parallel rank's share of a pre-norm transformer block, forward and backward, run the
+ * Domino way: the batch is cut into p independent row slices (paper Sec. 3.2 / 4.1, Eq. 3) and the
+ * second weight matrix of each sub-layer (attention out-projection, MLP down-projection) into q
+ * column slices (Sec. 3.3 / 4.2, Eq. 4); the p x q pieces (Sec. 3.4) are enqueued on a fixed pool of
+ * caller-provided HIP streams (Sec. 4.3.1).  The four all-reduces of a block (Sec. 2.3) are not
+ * performed: the tensors they would sum are outputs ("*_partial"), and what they would add from
+ * the other ranks are optional inputs ("*_others").
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers, 16-byte aligned, caller-owned; the library allocates
+ *     no device memory.  Activations are bf16, row-major [tokens, features] with tokens = batch*seq
+ *     (batch-major); weight matrices are bf16 row-major [in, out]; gradients of parameters are fp32.
+ *   - Streams are hipStream_t handles passed as void*.  Calls only enqueue work and return; on
+ *     return, everything is ordered before later work submitted to streams[0].  No host sync.
+ *   - Return value: DOMINO_OK or a negative DOMINO_ERR_*; domino_last_error() gives the text.
+ *     Arguments are validated before any GPU call, so invalid calls fail the same way on a host
+ *     without a GPU.  The library never throws and never aborts.
+ *   - Every single tensor must be smaller than 2 GiB (32-bit buffer offsets in the kernels).
+ */
+#ifndef DOMINO_H
+#define DOMINO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DOMINO_OK = 0,
+  DOMINO_ERR_INVALID_ARG = -1,         /* a scalar out of range */
+  DOMINO_ERR_INDIVISIBLE = -2,         /* batch % p, hidden % q, heads % tp, ffn % tp, hidden % heads */
+  DOMINO_ERR_NULL_POINTER = -3,
+  DOMINO_ERR_WORKSPACE_TOO_SMALL = -4,
+  DOMINO_ERR_UNSUPPORTED = -5,         /* head_dim not in {64, 80, 128}, dims not multiples of 8/32, ... */
+  DOMINO_ERR_HIP = -6                  /* a HIP runtime call failed (text holds hipGetErrorString) */
+};
+
+enum { DOMINO_ARCH_GPT = 0,            /* LayerNorm, biases, GeLU (op list of Sec. 4.1.1) */
+       DOMINO_ARCH_LLAMA = 1 };        /* RMSNorm, no biases, SwiGLU, rotary embedding (Sec. 5.4) */
+
+typedef struct domino_cfg {
+  int32_t hidden, heads, tp, rank;     /* h, n, tensor-parallel degree t, this rank r (Sec. 3.1) */
+  int32_t p, q;                        /* row slices p1 (Sec. 4.1.1), column slices p2 (Sec. 4.2) */
+  int32_t batch, seq, ffn;             /* b, s, FULL ffn width f (4h, 11008, ...) */
+  int32_t arch;                        /* DOMINO_ARCH_* */
+  int32_t gelu_tanh;                   /* 1 = tanh form (default), 0 = erf form */
+  float norm_eps;                      /* inside the square root; 1e-5 */
+  float rope_base;                     /* 10000 */
+} domino_cfg;
+
+/* Rank-local parameters.  h_l = hidden/tp, f_l = ffn/tp.
+ *   norm1_g/b, norm2_g/b [h]; w_qkv [h, 3*h_l] with column blocks [Q | K | V], heads contiguous inside a
+ *   block (rank r owns heads r*n/t .. (r+1)*n/t-1); b_qkv [3*h_l]; w_o [h_l, h]; b_o [h];
+ *   w_up [h, f_l] (GPT) or [h, 2*f_l] = [gate | up] (Llama); b_up [f_l]; w_down [f_l, h]; b_down [h].
+ * Llama: every *_b / b_* pointer must be NULL.  b_o and b_down belong to the reduced tensors: they are
+ * added once where the sum is consumed, never to the partials. */
+typedef struct domino_params {
+  const void *norm1_g, *norm1_b, *w_qkv, *b_qkv, *w_o, *b_o,
+             *norm2_g, *norm2_b, *w_up, *b_up, *w_down, *b_down;
+} domino_params;
+
+/* fp32 gradients, same shapes as domino_params (NULL where the parameter is NULL). */
+typedef struct domino_grads {
+  float *norm1_g, *norm1_b, *w_qkv, *b_qkv, *w_o, *b_o,
+        *norm2_g, *norm2_b, *w_up, *b_up, *w_down, *b_down;
+} domino_grads;
+
+/* Host-only checks of a configuration (no GPU call).  Returns DOMINO_OK or the error. */
+int domino_validate_cfg(const domino_cfg* cfg);
+
+/* Bytes of the activation block carried from forward to backward, and of the scratch workspace
+ * either call needs (0 on an invalid cfg).  Both are caller-allocated, 256-byte aligned. */
+size_t domino_saved_bytes(const domino_cfg* cfg);
+size_t domino_workspace_bytes(const domino_cfg* cfg);
+
+/* Byte offset and size of one named tensor inside the saved block (for inspection by tests):
+ * "ln1","qkv","ctx","lse","x1","ln2","pre","act","mean1","rstd1","mean2","rstd2".  Returns DOMINO_OK
+ * or DOMINO_ERR_INVALID_ARG for an unknown name. */
+int domino_saved_slot(const domino_cfg* cfg, const char* name, size_t* offset, size_t* bytes);
+
+/* Forward of the rank's block on x [b, s, h] (Sec. 3.1-3.4; schedule of Sec. 4.1.1 / 4.2).
+ * For each row slice i: Norm1, QKV product (never column-sliced, Sec. 3.1), causal attention, then per
+ * column slice j the out-projection piece written in place into attn_partial[rows_i, cols_j] (the
+ * concatenation of Sec. 4.2 without a copy); after all q pieces of slice i (the column
+ * synchronisation of Sec. 3.3): x1 = x + attn_partial + attn_others + b_o, Norm2, MLP-up with fused
+ * activation, per column slice j the down-projection piece into mlp_partial[rows_i, cols_j]; finally
+ * y = x1 + mlp_partial + mlp_others + b_down.
+ *   attn_others, mlp_others: [b,s,h] or NULL (= zeros): sum of the other ranks' partials.
+ *   attn_partial, mlp_partial: out [b,s,h]: what the two forward all-reduces would consume.
+ *   y: out [b,s,h] or NULL.   saved: out, domino_saved_bytes().   workspace: scratch.
+ *   streams[0..nstreams-1]: piece (i, j) runs on streams[(i + j*p) % nstreams]. */
+int domino_layer_fwd(const domino_cfg* cfg, const domino_params* params,
+                     const void* x, const void* attn_others, const void* mlp_others,
+                     void* attn_partial, void* mlp_partial, void* y,
+                     void* saved, void* workspace, size_t workspace_bytes,
+                     void* const* streams, int nstreams);
+
+/* Backward for L = sum(y * dy) (Sec. 4.1.2: per row slice, the input gradient of each product is
+ * formed before its weight gradient).  x and saved are those of the forward call.
+ *   dln2_others, dln1_others: [b,s,h] or NULL: the other ranks' sums of the two backward all-reduces.
+ *   dln2_partial, dln1_partial: out [b,s,h]: this rank's input gradients of MLP-up and QKV.
+ *   dx: out [b,s,h].   grads: fp32; accumulate != 0 adds to their contents, else overwrites.
+ * Weight gradients are summed over the row slices in slice order (run-to-run identical). */
+int domino_layer_bwd(const domino_cfg* cfg, const domino_params* params, const void* saved,
+                     const void* x, const void* dy,
+                     const void* dln2_others, const void* dln1_others,
+                     void* dln2_partial, void* dln1_partial, void* dx,
+                     const domino_grads* grads, int accumulate,
+                     void* workspace, size_t workspace_bytes,
+                     void* const* streams, int nstreams);
+
+/* ---- single kernels (the steps above, exposed for unit parity tests and roofline runs) ---------- */
+
+enum { DOMINO_GEMM_NN = 0,   /* C[M,N] = A[M,K] * B[K,N]        forward products (Eq. 1-4)            */
+       DOMINO_GEMM_NT = 1,   /* C[M,N] = A[M,K] * B[N,K]^T      input gradient  (Sec. 4.1.2)          */
+       DOMINO_GEMM_TN = 2 }; /* C[M,N] = A[K,M]^T * B[K,N]      weight gradient, C fp32 (Sec. 4.1.2)  */
+enum { DOMINO_EPI_STORE = 0,      /* C = bf16(acc + bias)                                    NN, NT */
+       DOMINO_EPI_BIAS_GELU = 1,  /* aux = bf16(acc + bias), C = GeLU(acc + bias)            NN     */
+       DOMINO_EPI_SWIGLU = 2,     /* B = [gate | up] (n_split columns each), N = n_split;
+                                     aux[M, 2*n_split] = [gate | up], C[M, n_split] = silu(gate)*up  NN */
+       DOMINO_EPI_DGELU = 3,      /* C = acc * GeLU'(aux)                                    NT     */
+       DOMINO_EPI_DSWIGLU = 4,    /* aux[M, 2*n_split] = saved [gate | up], N = n_split;
+                                     C[M, 2*n_split] = [acc*up*silu'(gate) | acc*silu(gate)]  NT     */
+       DOMINO_EPI_ACC_F32 = 5 };  /* C(fp32) = acc, or += acc if beta                        TN     */
+
+/* bf16 MFMA product with fp32 accumulation.  M, N, K and all leading dimensions (in elements) must be
+ * multiples of 8.  tile: -1 = choose by shape, 0 = 128x128, 1 = 256x128, 2 = 256x256 workgroup tile.
+ * bias: bf16 [N] or NULL.  Invalid layout/epilogue pairs return DOMINO_ERR_INVALID_ARG. */
+int domino_gemm(int layout, int epilogue, int tile,
+                const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                int M, int N, int K, const void* bias, void* aux, int64_t ldaux,
+                int n_split, int beta, int gelu_tanh, void* stream);
+
+/* y = Norm(x + add1 + add2 + vec): LayerNorm (rms = 0) or RMSNorm (rms = 1) over the last axis of
+ * [rows, h]; add1, add2 [rows, h], vec [h], beta [h], xsum (out: the pre-norm sum), mean may be NULL.
+ * mean, rstd: fp32 [rows].  h must be a multiple of 8 and at most 8192. */
+int domino_norm_fwd(const void* x, const void* add1, const void* add2, const void* vec,
+                    const void* gamma, const void* beta, void* xsum, void* y, float* mean, float* rstd,
+                    int rows, int h, int rms, float eps, void* stream);
+
+/* dx = dres + NormBwd(ga + gb) and the parameter gradients dgamma, dbeta (fp32 [h], overwritten;
+ * dbeta NULL for RMSNorm).  gb, dres may be NULL.  scratch: fp32, domino_norm_bwd_scratch_floats(rows, h). */
+size_t domino_norm_bwd_scratch_floats(int rows, int h);
+int domino_norm_bwd(const void* ga, const void* gb, const void* x, const void* gamma,
+                    const float* mean, const float* rstd, const void* dres, void* dx,
+                    float* dgamma, float* dbeta, float* scratch,
+                    int rows, int h, int rms, void* stream);
+
+/* Causal softmax(q k^T / sqrt(d)) v (Eq. 2, first case) per (batch element, local head), flash
+ * style (no seq x seq matrix in HBM).  qkv: bf16 [batch*seq, ld] with q of head hh at columns
+ * hh*d, k at heads*d + hh*d, v at 2*heads*d + hh*d.  ctx: out bf16 [batch*seq, heads*d];
+ * lse: out fp32 [batch, heads, seq], natural-log-sum-exp of the scaled masked scores.
+ * head_dim in {64, 80, 128}. */
+int domino_attention_fwd(const void* qkv, int64_t ld, int batch, int seq, int heads, int head_dim,
+                         void* ctx, float* lse, void* stream);
+
+/* Gradients of the above: dqkv (same layout as qkv) from dctx.  dot: fp32 scratch [batch, heads, seq]. */
+int domino_attention_bwd(const void* qkv, int64_t ld, const void* ctx, const void* dctx, const float* lse,
+                         void* dqkv, float* dot, int batch, int seq, int heads, int head_dim, void* stream);
+
+/* Rotary embedding in place on nblocks consecutive [heads*head_dim]-wide column blocks of
+ * m[rows, ld] starting at column col0 (pairs (i, i + d/2), angle pos * base^(-2i/d), pos = row % seq);
+ * inverse != 0 applies the transposed rotation. */
+int domino_rope(void* m, int64_t ld, int rows, int seq, int col0, int nblocks, int heads, int head_dim,
+                float base, int inverse, void* stream);
+
+/* out[n] (fp32) = column sums of the bf16 matrix g[rows, ld] (+= if accumulate).
+ * scratch: fp32, 64 * n floats. */
+int domino_colsum(const void* g, int64_t ld, int rows, int n, float* out, int accumulate,
+                  float* scratch, void* stream);
+
+/* ---- instrumentation -------------------------------------------------------------------------- */
+
+/* While enabled, every kernel launched by domino_layer_fwd/bwd is bracketed by a pair of timing
+ * events on its own stream.  domino_profile_read() synchronises those events and returns, for step
+ * class `cls` (0 .. domino_profile_classes()-1), the summed elapsed milliseconds and the launch count
+ * since the last domino_profile_reset().  Costs two event records per launch: keep it off when
+ * timing the whole layer. */
+int domino_profile_enable(int on);
+int domino_profile_classes(void);
+const char* domino_profile_name(int cls);
+int domino_profile_read(int cls, double* total_ms, int* launches);
+int domino_profile_reset(void);
+
+const char* domino_last_error(void);   /* thread-local, static storage */
+const char* domino_version(void);
+void domino_shutdown(void);            /* destroys cached events; the library stays usable */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DOMINO_H */

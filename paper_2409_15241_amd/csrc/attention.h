@@ -1,0 +1,19 @@
+// Internal launcher interface of the attention kernels (see attention.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+
+struct AttnArgs {
+  const void* qkv;     // bf16 [batch*seq, ld]: q | k | v column blocks, heads contiguous inside a block
+  long ld;
+  void* ctx;           // bf16 [batch*seq, ld_ctx]: forward output / backward input
+  long ld_ctx;
+  const void* dctx;    // bf16 [batch*seq, ld_ctx] (backward)
+  float* lse;          // fp32 [batch, heads, seq]
+  float* dot;          // fp32 [batch, heads, seq]: rowsum(dctx * ctx) (backward scratch)
+  void* dqkv;          // bf16 [batch*seq, ld] (backward output)
+  int batch, seq, heads, head_dim;
+  float scale;         // 1 / sqrt(head_dim)
+};
+
+hipError_t attention_fwd_launch(const AttnArgs& a, hipStream_t st);
+hipError_t attention_bwd_launch(const AttnArgs& a, hipStream_t st);

@@ -1,0 +1,64 @@
+// Shared device-side types and small helpers for the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define DEV __device__ __forceinline__
+
+// two floats -> packed bf16 pair, round-to-nearest-even (lo in bits 0..15)
+DEV uint32_t pack_bf16(float lo, float hi) {
+  bf16x2 p;
+  p[0] = (__bf16)lo;
+  p[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, p);
+}
+DEV float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+DEV float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+DEV float bf16_to_f32(bf16_t v) { return (float)v; }
+
+// tanh-form GeLU and its derivative (fp32); erf form selectable.
+DEV float fast_tanh(float x) {
+  // tanh(x) = 1 - 2/(exp(2x)+1); exp overflow gives the correct limit 1, underflow gives -1
+  float e = __expf(2.0f * x);
+  return 1.0f - 2.0f / (e + 1.0f);
+}
+DEV float gelu_f(float x, bool tanh_form) {
+  if (tanh_form) {
+    float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return 0.5f * x * (1.0f + fast_tanh(u));
+  }
+  return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f));
+}
+DEV float gelu_grad_f(float x, bool tanh_form) {
+  if (tanh_form) {
+    float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    float t = fast_tanh(u);
+    return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 0.134145f * x * x);
+  }
+  float cdf = 0.5f * (1.0f + erff(x * 0.7071067811865476f));
+  float pdf = __expf(-0.5f * x * x) * 0.3989422804014327f;
+  return cdf + x * pdf;
+}
+DEV float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
+
+// wave64 reductions over all lanes
+DEV float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+DEV float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}

@@ -1,0 +1,72 @@
+// Small HBM-bound element-wise kernels: rotary embedding and the block's final residual sum.
+#include "eltwise.h"
+#include "common.h"
+
+namespace {
+
+// One thread per (row, pair index i < d/2): the angle pos * base^(-2i/d) is computed once and the
+// rotation applied to the pair (i, i + d/2) of every head of every column block.
+__global__ __launch_bounds__(256)
+void rope_kernel(bf16_t* __restrict__ m, long ld, int rows, int seq, int col0, int nblocks, int heads, int d,
+                 float log2_base, int inverse) {
+  const int half = d >> 1;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)rows * half) return;
+  const int row = (int)(idx / half), i = (int)(idx % half);
+  const float pos = (float)(row % seq);
+  const float freq = exp2f(-2.0f * (float)i / (float)d * log2_base);
+  float sn, cs;
+  sincosf(pos * freq, &sn, &cs);
+  if (inverse) sn = -sn;
+  bf16_t* r = m + (long)row * ld + col0;
+  for (int blk = 0; blk < nblocks; ++blk)
+    for (int hh = 0; hh < heads; ++hh) {
+      bf16_t* p = r + (blk * heads + hh) * d + i;
+      const float a = (float)p[0], b = (float)p[half];
+      p[0] = (bf16_t)(a * cs - b * sn);
+      p[half] = (bf16_t)(b * cs + a * sn);
+    }
+}
+
+__global__ __launch_bounds__(256)
+void residual_out_kernel(const u32x4* __restrict__ x1, const u32x4* __restrict__ a, const u32x4* __restrict__ b,
+                         const u32x4* __restrict__ vec, u32x4* __restrict__ y, long nchunks, int hch) {
+  const long c = (long)blockIdx.x * 256 + threadIdx.x;
+  if (c >= nchunks) return;
+  const u32x4 vx = x1[c], va = a[c];
+  float f[8] = {bf16_lo(vx[0]) + bf16_lo(va[0]), bf16_hi(vx[0]) + bf16_hi(va[0]),
+                bf16_lo(vx[1]) + bf16_lo(va[1]), bf16_hi(vx[1]) + bf16_hi(va[1]),
+                bf16_lo(vx[2]) + bf16_lo(va[2]), bf16_hi(vx[2]) + bf16_hi(va[2]),
+                bf16_lo(vx[3]) + bf16_lo(va[3]), bf16_hi(vx[3]) + bf16_hi(va[3])};
+  if (b) {
+    const u32x4 v = b[c];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { f[2 * e] += bf16_lo(v[e]); f[2 * e + 1] += bf16_hi(v[e]); }
+  }
+  if (vec) {
+    const u32x4 v = vec[c % hch];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { f[2 * e] += bf16_lo(v[e]); f[2 * e + 1] += bf16_hi(v[e]); }
+  }
+  u32x4 o = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
+  y[c] = o;
+}
+
+}  // namespace
+
+hipError_t rope_launch(void* m, long ld, int rows, int seq, int col0, int nblocks, int heads, int d,
+                       float base, int inverse, hipStream_t st) {
+  const long n = (long)rows * (d / 2);
+  hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                     static_cast<bf16_t*>(m), ld, rows, seq, col0, nblocks, heads, d, log2f(base), inverse);
+  return hipGetLastError();
+}
+
+hipError_t residual_out_launch(const void* x1, const void* a, const void* b, const void* vec, void* y,
+                               long n_elems, int h, hipStream_t st) {
+  const long nch = n_elems / 8;
+  hipLaunchKernelGGL(residual_out_kernel, dim3((unsigned)((nch + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const u32x4*>(x1), static_cast<const u32x4*>(a), static_cast<const u32x4*>(b),
+                     static_cast<const u32x4*>(vec), static_cast<u32x4*>(y), nch, h / 8);
+  return hipGetLastError();
+}

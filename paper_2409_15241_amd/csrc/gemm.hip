@@ -1,0 +1,256 @@
+// bf16 MFMA GEMM for gfx950 with fused epilogues: the products of Eq. 1-4 (X*A, (XA)*B_j) and the
+// two products of every "grad matmul" (Sec. 4.1.2: input gradient and weight gradient).
+//
+//   C[m][n] = epilogue( sum_k Aop(m,k) * Bop(k,n) ),  fp32 accumulation in MFMA 32x32x16.
+//
+// Each operand is either contraction-contiguous in memory (KC: [row][k]) or contraction-strided
+// (KS: [k][row]); see lds_tile.h.  The three products of a linear layer map to
+//   forward   X[M,K]   * W[K,N]            : A KC, B KS
+//   dgrad     dY[M,N'] * W[K',N']^T        : A KC, B KC   (contraction over N')
+//   wgrad     X[M',K']^T * dY[M',N]        : A KS, B KS   (contraction over the tokens M')
+//
+// Work decomposition: one workgroup per BM x BN tile of C, (BM/WM)*(BN/WN) waves, each owning a
+// WM x WN sub-tile as (WN/32) x (WM/32) MFMA accumulators.  Operand tiles of 64 contraction
+// elements are double-buffered in LDS: the next tile's global loads are issued before the MFMA
+// loop of the current one and written to the other buffer after it (one barrier per step).
+// The MFMA is issued with the roles swapped (first operand = B fragment) so that a lane ends up
+// with 4 consecutive n for one m: 8-byte bf16 / 16-byte fp32 stores.
+#include "gemm.h"
+#include "lds_tile.h"
+
+namespace {
+
+template <int BM, int BN, int WM, int WN, bool AKS, bool BKS, int EPI>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64)
+void gemm_kernel(const GemmArgs p) {
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int A_BYTES = BM * TILE_ROW_BYTES, B_BYTES = BN * TILE_ROW_BYTES;
+  constexpr int STAGE = A_BYTES + B_BYTES;
+  extern __shared__ __align__(16) uint8_t smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave % (BM / WM)) * WM, wn0 = (wave / (BM / WM)) * WN;
+
+  // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give every XCD a
+  // contiguous run of tiles (they share operand tiles through that XCD's L2).
+  const int per_xcd = (p.tiles_m * p.tiles_n + 7) >> 3;
+  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (tile >= p.tiles_m * p.tiles_n) return;
+  const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const buf_rsrc A = make_rsrc(p.A, p.a_bytes);
+  const buf_rsrc B = make_rsrc(p.B, p.b_bytes);
+
+  // SwiGLU forward: the tile's even 32-column groups are gate columns, the odd ones the matching
+  // up columns, so one lane sees gate and up of the same ffn column.
+  struct GluCols {
+    int c0, n_split;
+    DEV int operator()(int r) const {
+      int col = c0 + ((r >> 6) << 5) + (r & 31);
+      if (col >= n_split) return -1;
+      return col + ((r >> 5) & 1) * n_split;
+    }
+  };
+
+  typename std::conditional<AKS, MoverKS<BM, NT>, MoverKC<BM, NT>>::type mvA;
+  typename std::conditional<BKS, MoverKS<BN, NT>, MoverKC<BN, NT>>::type mvB;
+
+  if constexpr (AKS) mvA.init((int)p.lda, IdentityCols{m0, p.M}, tid);
+  else mvA.init((int)p.lda, m0, p.M, tid);
+  if constexpr (BKS) {
+    if constexpr (EPI == EPI_SWIGLU) mvB.init((int)p.ldb, GluCols{tn * (BN / 2), p.n_split}, tid);
+    else mvB.init((int)p.ldb, IdentityCols{n0, p.N}, tid);
+  } else {
+    mvB.init((int)p.ldb, n0, p.N, tid);
+  }
+  auto load_tiles = [&](int k0) {
+    mvA.load(A, k0, p.K);
+    mvB.load(B, k0, p.K);
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int nk = (p.K + TILE_K - 1) / TILE_K;
+  load_tiles(0);
+  mvA.store(smem, tid);
+  mvB.store(smem + A_BYTES, tid);
+  __syncthreads();
+
+  const int fr = lane & 31, fh = lane >> 5;
+  for (int kt = 0; kt < nk; ++kt) {
+    const uint8_t* sA = smem + (kt & 1) * STAGE;
+    const uint8_t* sB = sA + A_BYTES;
+    if (kt + 1 < nk) load_tiles((kt + 1) * TILE_K);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int j = 0; j < TM; ++j) fa[j] = lds_read_frag<AKS>(sA, wm0 + j * 32 + fr, 2 * ks + fh);
+#pragma unroll
+      for (int i = 0; i < TN; ++i) fb[i] = lds_read_frag<BKS>(sB, wn0 + i * 32 + fr, 2 * ks + fh);
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      uint8_t* dA = smem + ((kt + 1) & 1) * STAGE;
+      mvA.store(dA, tid);
+      mvB.store(dA + A_BYTES, tid);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulator (i, j) value v is C[m][n] with
+  //      m = m0 + wm0 + 32 j + lane%32,  n = n0 + wn0 + 32 i + 8 (v/4) + 4 (lane/32) + v%4
+  const bool tanh_form = p.gelu_tanh != 0;
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int m = m0 + wm0 + j * 32 + fr;
+    if (m >= p.M) continue;
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int nl = wn0 + i * 32 + g * 8 + fh * 4;   // tile-local column of the first of 4
+        f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        if constexpr (EPI == EPI_SWIGLU) {
+          if (i & 1) continue;                          // handled together with its gate group
+          const int col = tn * (BN / 2) + ((nl >> 6) << 5) + (nl & 31);
+          if (col >= p.n_split) continue;
+          f32x4 u = {acc[i + 1][j][4 * g], acc[i + 1][j][4 * g + 1], acc[i + 1][j][4 * g + 2], acc[i + 1][j][4 * g + 3]};
+          bf16_t* aux = static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux;
+          u32x2 pg = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+          u32x2 pu = {pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
+          *reinterpret_cast<u32x2*>(aux + col) = pg;
+          *reinterpret_cast<u32x2*>(aux + p.n_split + col) = pu;
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = v[e] * sigmoid_f(v[e]) * u[e];
+          u32x2 po = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+          *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + col) = po;
+        } else {
+          const int n = n0 + nl;
+          if (n >= p.N) continue;
+          if constexpr (EPI == EPI_ACC_F32) {
+            float* c = static_cast<float*>(p.C) + (long)m * p.ldc + n;
+            if (p.beta) {
+              f32x4 old = *reinterpret_cast<const f32x4*>(c);
+              v += old;
+            }
+            *reinterpret_cast<f32x4*>(c) = v;
+          } else {
+            if (p.bias) {
+              const u32x2 bb = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.bias) + n);
+              v[0] += bf16_lo(bb[0]); v[1] += bf16_hi(bb[0]); v[2] += bf16_lo(bb[1]); v[3] += bf16_hi(bb[1]);
+            }
+            if constexpr (EPI == EPI_BIAS_GELU) {
+              u32x2 pp = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux + n) = pp;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e], tanh_form);
+            } else if constexpr (EPI == EPI_DGELU) {
+              const u32x2 pp = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux + n);
+              v[0] *= gelu_grad_f(bf16_lo(pp[0]), tanh_form); v[1] *= gelu_grad_f(bf16_hi(pp[0]), tanh_form);
+              v[2] *= gelu_grad_f(bf16_lo(pp[1]), tanh_form); v[3] *= gelu_grad_f(bf16_hi(pp[1]), tanh_form);
+            } else if constexpr (EPI == EPI_DSWIGLU) {
+              const bf16_t* aux = static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux;
+              const u32x2 pg = *reinterpret_cast<const u32x2*>(aux + n);
+              const u32x2 pu = *reinterpret_cast<const u32x2*>(aux + p.n_split + n);
+              const float gv[4] = {bf16_lo(pg[0]), bf16_hi(pg[0]), bf16_lo(pg[1]), bf16_hi(pg[1])};
+              const float uv[4] = {bf16_lo(pu[0]), bf16_hi(pu[0]), bf16_lo(pu[1]), bf16_hi(pu[1])};
+              f32x4 du;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float sg = sigmoid_f(gv[e]);
+                du[e] = v[e] * gv[e] * sg;                                   // d_act * silu(g)
+                v[e] = v[e] * uv[e] * sg * (1.0f + gv[e] * (1.0f - sg));     // d_act * u * silu'(g)
+              }
+              u32x2 pdu = {pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
+              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + p.n_split + n) = pdu;
+            }
+            u32x2 po = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + n) = po;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN, bool AKS, bool BKS, int EPI>
+hipError_t launch_cfg(const GemmArgs& a0, hipStream_t stream) {
+  GemmArgs a = a0;
+  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr int LDS = 2 * (BM + BN) * TILE_ROW_BYTES;
+  const int n_logical = (EPI == EPI_SWIGLU) ? 2 * a.n_split : a.N;
+  a.tiles_m = (a.M + BM - 1) / BM;
+  a.a_bytes = AKS ? ((long)(a.K - 1) * a.lda + a.M) * 2 : ((long)(a.M - 1) * a.lda + a.K) * 2;
+  a.b_bytes = BKS ? ((long)(a.K - 1) * a.ldb + n_logical) * 2 : ((long)(a.N - 1) * a.ldb + a.K) * 2;
+  if (a.a_bytes >= (1L << 31) || a.b_bytes >= (1L << 31)) return hipErrorInvalidValue;
+  a.tiles_n = (n_logical + BN - 1) / BN;
+  auto kern = gemm_kernel<BM, BN, WM, WN, AKS, BKS, EPI>;
+  static bool attr_done = false;      // one flag per instantiation
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int per_xcd = (a.tiles_m * a.tiles_n + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(NT), LDS, stream, a);
+  return hipGetLastError();
+}
+
+template <bool AKS, bool BKS, int EPI>
+hipError_t launch_layout(const GemmArgs& a, int tile_cfg, hipStream_t stream) {
+  switch (tile_cfg) {
+    case GEMM_TILE_256x256: return launch_cfg<256, 256, 128, 64, AKS, BKS, EPI>(a, stream);
+    case GEMM_TILE_256x128: return launch_cfg<256, 128, 128, 64, AKS, BKS, EPI>(a, stream);
+    default:                return launch_cfg<128, 128, 64, 64, AKS, BKS, EPI>(a, stream);
+  }
+}
+
+}  // namespace
+
+int gemm_pick_tile(int M, int N) {
+  // Big tiles need enough of them to cover the 256 CUs; otherwise fall back to smaller ones.
+  const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (t256 >= 48) return GEMM_TILE_256x256;
+  const long t128 = (long)((M + 255) / 256) * ((N + 127) / 128);
+  if (t128 >= 48) return GEMM_TILE_256x128;
+  return GEMM_TILE_128x128;
+}
+
+hipError_t gemm_launch(int layout, int epi, const GemmArgs& a, int tile_cfg, hipStream_t stream) {
+  if (tile_cfg < 0) tile_cfg = gemm_pick_tile(a.M, epi == EPI_SWIGLU ? 2 * a.n_split : a.N);
+  if (layout == GEMM_NN) {
+    switch (epi) {
+      case EPI_STORE:     return launch_layout<false, true, EPI_STORE>(a, tile_cfg, stream);
+      case EPI_BIAS_GELU: return launch_layout<false, true, EPI_BIAS_GELU>(a, tile_cfg, stream);
+      case EPI_SWIGLU:    return launch_layout<false, true, EPI_SWIGLU>(a, tile_cfg, stream);
+      default: return hipErrorInvalidValue;
+    }
+  } else if (layout == GEMM_NT) {
+    switch (epi) {
+      case EPI_STORE:   return launch_layout<false, false, EPI_STORE>(a, tile_cfg, stream);
+      case EPI_DGELU:   return launch_layout<false, false, EPI_DGELU>(a, tile_cfg, stream);
+      case EPI_DSWIGLU: return launch_layout<false, false, EPI_DSWIGLU>(a, tile_cfg, stream);
+      default: return hipErrorInvalidValue;
+    }
+  } else if (layout == GEMM_TN) {
+    if (epi == EPI_ACC_F32) return launch_layout<true, true, EPI_ACC_F32>(a, tile_cfg, stream);
+    return hipErrorInvalidValue;
+  }
+  return hipErrorInvalidValue;
+}
