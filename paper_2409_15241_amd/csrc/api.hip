@@ -1,0 +1,702 @@
+// Host side of the C ABI declared in include/domino.h: argument validation, memory layout of the
+// saved / workspace blocks, the p x q piece schedule over the caller's stream pool, and the
+// single-kernel entry points.  No device memory is allocated here and no host synchronisation is
+// performed by the layer calls.
+#include "../../include/domino.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "attention.h"
+#include "eltwise.h"
+#include "gemm.h"
+#include "norm.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+int fail_hip(hipError_t e, const char* what) {
+  return fail(DOMINO_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+#define HIP_TRY(expr, what)                                  \
+  do {                                                       \
+    hipError_t e_ = (expr);                                  \
+    if (e_ != hipSuccess) return fail_hip(e_, what);         \
+  } while (0)
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+constexpr long TWO_GIB = 1L << 31;
+
+// ---------------------------------------------------------------------------------- layout
+struct Layout {
+  int h, n, t, r, p, q, b, s, f, d, nl, hl, fl, upc, M, Ms, hq;
+  bool llama;
+  // saved block (bytes)
+  size_t ln1, qkv, ctx, lse, x1, ln2, pre, act, mean1, rstd1, mean2, rstd2, saved_total;
+  // workspace block (bytes)
+  size_t d_pre, dx1, dctx, dqkv, dot, red, slots, ws_total;
+  size_t red_floats, slot_floats;   // per-slice reduction scratch; one slot vector
+};
+
+enum { SLOT_G1 = 0, SLOT_B1, SLOT_G2, SLOT_B2, SLOT_BQKV, SLOT_BO, SLOT_BUP, SLOT_BDOWN, NSLOTS };
+
+int validate(const domino_cfg* c, Layout* L) {
+  if (!c) return fail(DOMINO_ERR_NULL_POINTER, "cfg is NULL");
+  if (c->hidden <= 0 || c->heads <= 0 || c->tp <= 0 || c->p <= 0 || c->q <= 0 || c->batch <= 0 ||
+      c->seq <= 0 || c->ffn <= 0)
+    return fail(DOMINO_ERR_INVALID_ARG, "hidden, heads, tp, p, q, batch, seq, ffn must be positive");
+  if (c->rank < 0 || c->rank >= c->tp) return fail(DOMINO_ERR_INVALID_ARG, "rank %d outside [0, tp=%d)", c->rank, c->tp);
+  if (c->arch != DOMINO_ARCH_GPT && c->arch != DOMINO_ARCH_LLAMA)
+    return fail(DOMINO_ERR_INVALID_ARG, "arch %d is neither GPT (0) nor Llama (1)", c->arch);
+  if (!(c->norm_eps > 0.0f) || !(c->norm_eps < 1.0f)) return fail(DOMINO_ERR_INVALID_ARG, "norm_eps must lie in (0, 1)");
+  if (c->arch == DOMINO_ARCH_LLAMA && !(c->rope_base > 1.0f)) return fail(DOMINO_ERR_INVALID_ARG, "rope_base must exceed 1");
+  if (c->hidden % c->heads) return fail(DOMINO_ERR_INDIVISIBLE, "hidden %d %% heads %d != 0", c->hidden, c->heads);
+  if (c->heads % c->tp) return fail(DOMINO_ERR_INDIVISIBLE, "heads %d %% tp %d != 0", c->heads, c->tp);
+  if (c->ffn % c->tp) return fail(DOMINO_ERR_INDIVISIBLE, "ffn %d %% tp %d != 0", c->ffn, c->tp);
+  if (c->batch % c->p) return fail(DOMINO_ERR_INDIVISIBLE, "batch %d %% p %d != 0", c->batch, c->p);
+  if (c->hidden % c->q) return fail(DOMINO_ERR_INDIVISIBLE, "hidden %d %% q %d != 0", c->hidden, c->q);
+  Layout l{};
+  l.h = c->hidden; l.n = c->heads; l.t = c->tp; l.r = c->rank; l.p = c->p; l.q = c->q;
+  l.b = c->batch; l.s = c->seq; l.f = c->ffn;
+  l.llama = c->arch == DOMINO_ARCH_LLAMA;
+  l.d = l.h / l.n; l.nl = l.n / l.t; l.hl = l.nl * l.d; l.fl = l.f / l.t;
+  l.upc = l.fl * (l.llama ? 2 : 1);
+  l.hq = l.h / l.q;
+  if (l.d != 64 && l.d != 80 && l.d != 128) return fail(DOMINO_ERR_UNSUPPORTED, "head_dim %d not in {64, 80, 128}", l.d);
+  if (l.h % 8 || l.hq % 8 || l.fl % 8) return fail(DOMINO_ERR_UNSUPPORTED, "hidden, hidden/q and ffn/tp must be multiples of 8");
+  if (l.llama && l.fl % 32) return fail(DOMINO_ERR_UNSUPPORTED, "SwiGLU needs ffn/tp to be a multiple of 32");
+  if (l.h > 8192) return fail(DOMINO_ERR_UNSUPPORTED, "hidden %d exceeds 8192", l.h);
+  const long M = (long)l.b * l.s;
+  long widest = l.h;
+  if (3 * l.hl > widest) widest = 3 * l.hl;
+  if (l.upc > widest) widest = l.upc;
+  if (M * widest * 2 >= TWO_GIB) return fail(DOMINO_ERR_UNSUPPORTED, "an activation tensor would reach 2 GiB");
+  if ((long)l.h * widest * 4 >= TWO_GIB) return fail(DOMINO_ERR_UNSUPPORTED, "a weight-gradient tensor would reach 2 GiB");
+  l.M = (int)M;
+  l.Ms = l.M / l.p;
+
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
+  const size_t Mz = (size_t)l.M;
+  l.ln1 = take(Mz * l.h * 2);
+  l.qkv = take(Mz * 3 * l.hl * 2);
+  l.ctx = take(Mz * l.hl * 2);
+  l.lse = take((size_t)l.b * l.nl * l.s * 4);
+  l.x1 = take(Mz * l.h * 2);
+  l.ln2 = take(Mz * l.h * 2);
+  l.pre = take(Mz * l.upc * 2);
+  l.act = take(Mz * l.fl * 2);
+  l.mean1 = take(Mz * 4); l.rstd1 = take(Mz * 4); l.mean2 = take(Mz * 4); l.rstd2 = take(Mz * 4);
+  l.saved_total = o;
+
+  o = 0;
+  l.d_pre = take(Mz * l.upc * 2);
+  l.dx1 = take(Mz * l.h * 2);
+  l.dctx = take(Mz * l.hl * 2);
+  l.dqkv = take(Mz * 3 * l.hl * 2);
+  l.dot = take((size_t)l.b * l.nl * l.s * 4);
+  const size_t norm_fl = 2 * (size_t)norm_bwd_blocks(l.Ms) * l.h;
+  const size_t col_fl = (size_t)COLSUM_PARTS * widest;
+  l.red_floats = norm_fl > col_fl ? norm_fl : col_fl;
+  l.slot_floats = (size_t)widest;
+  l.red = take((size_t)l.p * l.red_floats * 4);
+  l.slots = take((size_t)l.p * NSLOTS * l.slot_floats * 4);
+  l.ws_total = o;
+  if (L) *L = l;
+  return DOMINO_OK;
+}
+
+// ---------------------------------------------------------------------------------- events, profiling
+std::mutex g_mutex;
+std::vector<hipEvent_t> g_sync_events;     // timing disabled, for cross-stream edges
+size_t g_sync_used = 0;
+
+int next_sync_event(hipEvent_t* ev) {
+  if (g_sync_used == g_sync_events.size()) {
+    hipEvent_t e;
+    HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
+    g_sync_events.push_back(e);
+  }
+  *ev = g_sync_events[g_sync_used++];
+  return DOMINO_OK;
+}
+
+enum ProfClass {
+  PC_NORM_FWD = 0, PC_GEMM_QKV, PC_ROPE, PC_ATTN_FWD, PC_GEMM_OUT, PC_GEMM_UP, PC_GEMM_DOWN, PC_RESID_OUT,
+  PC_DGRAD_DOWN, PC_WGRAD_DOWN, PC_DGRAD_UP, PC_WGRAD_UP, PC_NORM_BWD, PC_DGRAD_OUT, PC_WGRAD_OUT,
+  PC_ATTN_BWD, PC_DGRAD_QKV, PC_WGRAD_QKV, PC_COLSUM, PC_COUNT
+};
+const char* const PROF_NAMES[PC_COUNT] = {
+  "norm_fwd", "gemm_qkv", "rope", "attn_fwd", "gemm_out", "gemm_up", "gemm_down", "residual_out",
+  "dgrad_down", "wgrad_down", "dgrad_up", "wgrad_up", "norm_bwd", "dgrad_out", "wgrad_out",
+  "attn_bwd", "dgrad_qkv", "wgrad_qkv", "colsum"};
+
+struct ProfRec { int cls; hipEvent_t start, stop; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_recs;
+std::vector<hipEvent_t> g_prof_free;
+
+int prof_event(hipEvent_t* ev) {
+  if (!g_prof_free.empty()) { *ev = g_prof_free.back(); g_prof_free.pop_back(); return DOMINO_OK; }
+  HIP_TRY(hipEventCreate(ev), "hipEventCreate");
+  return DOMINO_OK;
+}
+
+// RAII bracket around the launches of one step on one stream
+struct ProfScope {
+  int cls; hipStream_t st; hipEvent_t start{}, stop{}; bool live = false;
+  ProfScope(int c, hipStream_t s) : cls(c), st(s) {
+    if (!g_prof_on) return;
+    if (prof_event(&start) != DOMINO_OK || prof_event(&stop) != DOMINO_OK) return;
+    if (hipEventRecord(start, st) != hipSuccess) return;
+    live = true;
+  }
+  ~ProfScope() {
+    if (!live) return;
+    (void)hipEventRecord(stop, st);
+    g_prof_recs.push_back({cls, start, stop});
+  }
+};
+
+inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+inline const char* at(const void* base, size_t off) { return static_cast<const char*>(base) + off; }
+inline char* at(void* base, size_t off) { return static_cast<char*>(base) + off; }
+
+GemmArgs gemm_args(const void* A, long lda, const void* B, long ldb, void* C, long ldc, int M, int N, int K) {
+  GemmArgs a{};
+  a.A = A; a.B = B; a.C = C; a.lda = lda; a.ldb = ldb; a.ldc = ldc; a.M = M; a.N = N; a.K = K;
+  a.gelu_tanh = 1;
+  return a;
+}
+
+// edge: work submitted later to `to` waits for everything submitted so far to `from`
+int edge(hipStream_t from, hipStream_t to) {
+  if (from == to) return DOMINO_OK;
+  hipEvent_t ev;
+  int rc = next_sync_event(&ev);
+  if (rc != DOMINO_OK) return rc;
+  HIP_TRY(hipEventRecord(ev, from), "hipEventRecord");
+  HIP_TRY(hipStreamWaitEvent(to, ev, 0), "hipStreamWaitEvent");
+  return DOMINO_OK;
+}
+
+#define TRY(expr)                      \
+  do {                                 \
+    int rc_ = (expr);                  \
+    if (rc_ != DOMINO_OK) return rc_;  \
+  } while (0)
+#define LAUNCH(expr, what) HIP_TRY((expr), what)
+
+int check_streams(void* const* streams, int nstreams) {
+  if (!streams) return fail(DOMINO_ERR_NULL_POINTER, "streams is NULL");
+  if (nstreams < 1 || nstreams > 64) return fail(DOMINO_ERR_INVALID_ARG, "nstreams %d outside [1, 64]", nstreams);
+  return DOMINO_OK;
+}
+
+int check_params(const Layout& L, const domino_params* P) {
+  if (!P) return fail(DOMINO_ERR_NULL_POINTER, "params is NULL");
+  if (!P->norm1_g || !P->norm2_g || !P->w_qkv || !P->w_o || !P->w_up || !P->w_down)
+    return fail(DOMINO_ERR_NULL_POINTER, "a weight matrix or norm gain pointer is NULL");
+  if (L.llama) {
+    if (P->norm1_b || P->norm2_b || P->b_qkv || P->b_o || P->b_up || P->b_down)
+      return fail(DOMINO_ERR_INVALID_ARG, "the Llama architecture has no shifts or biases: those pointers must be NULL");
+  } else if (!P->norm1_b || !P->norm2_b || !P->b_qkv || !P->b_o || !P->b_up || !P->b_down) {
+    return fail(DOMINO_ERR_NULL_POINTER, "a GPT bias or norm shift pointer is NULL");
+  }
+  return DOMINO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* domino_last_error(void) { return g_err; }
+const char* domino_version(void) { return "domino-mi355x 0.1 (gfx950)"; }
+
+int domino_validate_cfg(const domino_cfg* cfg) { return validate(cfg, nullptr); }
+
+size_t domino_saved_bytes(const domino_cfg* cfg) {
+  Layout L;
+  return validate(cfg, &L) == DOMINO_OK ? L.saved_total : 0;
+}
+size_t domino_workspace_bytes(const domino_cfg* cfg) {
+  Layout L;
+  return validate(cfg, &L) == DOMINO_OK ? L.ws_total : 0;
+}
+
+int domino_saved_slot(const domino_cfg* cfg, const char* name, size_t* offset, size_t* bytes) {
+  Layout L;
+  TRY(validate(cfg, &L));
+  if (!name || !offset || !bytes) return fail(DOMINO_ERR_NULL_POINTER, "name, offset or bytes is NULL");
+  const size_t Mz = (size_t)L.M;
+  struct { const char* n; size_t off, sz; } tab[] = {
+    {"ln1", L.ln1, Mz * L.h * 2}, {"qkv", L.qkv, Mz * 3 * L.hl * 2}, {"ctx", L.ctx, Mz * L.hl * 2},
+    {"lse", L.lse, (size_t)L.b * L.nl * L.s * 4}, {"x1", L.x1, Mz * L.h * 2}, {"ln2", L.ln2, Mz * L.h * 2},
+    {"pre", L.pre, Mz * L.upc * 2}, {"act", L.act, Mz * L.fl * 2}, {"mean1", L.mean1, Mz * 4},
+    {"rstd1", L.rstd1, Mz * 4}, {"mean2", L.mean2, Mz * 4}, {"rstd2", L.rstd2, Mz * 4}};
+  for (auto& e : tab)
+    if (!strcmp(e.n, name)) { *offset = e.off; *bytes = e.sz; return DOMINO_OK; }
+  return fail(DOMINO_ERR_INVALID_ARG, "unknown saved tensor '%s'", name);
+}
+
+// ------------------------------------------------------------------------------------ forward
+int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
+                     const void* x, const void* attn_others, const void* mlp_others,
+                     void* attn_partial, void* mlp_partial, void* y,
+                     void* saved, void* workspace, size_t workspace_bytes,
+                     void* const* streams, int nstreams) {
+  Layout L;
+  TRY(validate(cfg, &L));
+  TRY(check_params(L, P));
+  TRY(check_streams(streams, nstreams));
+  if (!x || !attn_partial || !mlp_partial || !saved) return fail(DOMINO_ERR_NULL_POINTER, "x, attn_partial, mlp_partial or saved is NULL");
+  if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
+  if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
+  std::lock_guard<std::mutex> lock(g_mutex);
+  g_sync_used = 0;
+
+  const int ns = nstreams;
+  hipStream_t s0 = as_stream(streams[0]);
+  std::vector<char> used(ns, 0);
+  for (int i = 0; i < L.p; ++i)
+    for (int j = 0; j < L.q; ++j) used[(i + j * L.p) % ns] = 1;
+  for (int k = 1; k < ns; ++k)
+    if (used[k]) TRY(edge(s0, as_stream(streams[k])));
+
+  const int Ms = L.Ms;
+  const bool rms = L.llama;
+  for (int i = 0; i < L.p; ++i) {
+    hipStream_t st = as_stream(streams[i % ns]);
+    const size_t r0 = (size_t)i * Ms;                       // first token row of the slice
+    const size_t rh = r0 * L.h * 2;                         // byte offset into [M, h] bf16 tensors
+    const char* xi = at(x, rh);
+    char* ln1 = at(saved, L.ln1 + rh);
+    char* qkv = at(saved, L.qkv + r0 * 3 * L.hl * 2);
+    char* ctx = at(saved, L.ctx + r0 * L.hl * 2);
+    float* lse = reinterpret_cast<float*>(at(saved, L.lse)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
+    char* x1 = at(saved, L.x1 + rh);
+    char* ln2 = at(saved, L.ln2 + rh);
+    char* pre = at(saved, L.pre + r0 * L.upc * 2);
+    char* act = at(saved, L.act + r0 * L.fl * 2);
+    float* mean1 = reinterpret_cast<float*>(at(saved, L.mean1)) + r0;
+    float* rstd1 = reinterpret_cast<float*>(at(saved, L.rstd1)) + r0;
+    float* mean2 = reinterpret_cast<float*>(at(saved, L.mean2)) + r0;
+    float* rstd2 = reinterpret_cast<float*>(at(saved, L.rstd2)) + r0;
+
+    {  // F1: Norm1
+      ProfScope ps(PC_NORM_FWD, st);
+      NormFwdArgs a{};
+      a.x = xi; a.gamma = P->norm1_g; a.beta = P->norm1_b; a.y = ln1; a.mean = rms ? nullptr : mean1; a.rstd = rstd1;
+      a.rows = Ms; a.h = L.h; a.rms = rms; a.eps = cfg->norm_eps;
+      LAUNCH(norm_fwd_launch(a, st), "norm1 forward");
+    }
+    {  // F2: X * A (attention), column-parallel, never column-sliced
+      ProfScope ps(PC_GEMM_QKV, st);
+      GemmArgs a = gemm_args(ln1, L.h, P->w_qkv, 3 * L.hl, qkv, 3 * L.hl, Ms, 3 * L.hl, L.h);
+      a.bias = P->b_qkv;
+      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "qkv product");
+    }
+    if (L.llama) {
+      ProfScope ps(PC_ROPE, st);
+      LAUNCH(rope_launch(qkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 0, st), "rotary embedding");
+    }
+    {  // F3
+      ProfScope ps(PC_ATTN_FWD, st);
+      AttnArgs a{};
+      a.qkv = qkv; a.ld = 3 * L.hl; a.ctx = ctx; a.ld_ctx = L.hl; a.lse = lse;
+      a.batch = L.b / L.p; a.seq = L.s; a.heads = L.nl; a.head_dim = L.d; a.scale = 1.0f / sqrtf((float)L.d);
+      LAUNCH(attention_fwd_launch(a, st), "attention forward");
+    }
+    // F4: (XA) * B_j, one piece per column slice, written in place into the full-width buffer
+    for (int j = 0; j < L.q; ++j) {
+      hipStream_t sj = as_stream(streams[(i + j * L.p) % ns]);
+      TRY(edge(st, sj));
+      {
+        ProfScope ps(PC_GEMM_OUT, sj);
+        const size_t cj = (size_t)j * L.hq * 2;
+        GemmArgs a = gemm_args(ctx, L.hl, at(P->w_o, cj), L.h, at(attn_partial, rh + cj), L.h, Ms, L.hq, L.hl);
+        LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "out-projection piece");
+      }
+      TRY(edge(sj, st));                                    // column synchronisation before Norm2
+    }
+    {  // F5: residual + reduced attention output + Norm2
+      ProfScope ps(PC_NORM_FWD, st);
+      NormFwdArgs a{};
+      a.x = xi; a.add1 = at(attn_partial, rh); a.add2 = attn_others ? at(attn_others, rh) : nullptr; a.vec = P->b_o;
+      a.gamma = P->norm2_g; a.beta = P->norm2_b; a.xsum = x1; a.y = ln2; a.mean = rms ? nullptr : mean2; a.rstd = rstd2;
+      a.rows = Ms; a.h = L.h; a.rms = rms; a.eps = cfg->norm_eps;
+      LAUNCH(norm_fwd_launch(a, st), "norm2 forward");
+    }
+    {  // F6: X * A (MLP) with the activation fused
+      ProfScope ps(PC_GEMM_UP, st);
+      GemmArgs a = gemm_args(ln2, L.h, P->w_up, L.upc, act, L.fl, Ms, L.fl, L.h);
+      a.aux = pre; a.ldaux = L.upc; a.gelu_tanh = cfg->gelu_tanh;
+      if (L.llama) { a.n_split = L.fl; LAUNCH(gemm_launch(GEMM_NN, EPI_SWIGLU, a, -1, st), "mlp-up product"); }
+      else { a.bias = P->b_up; LAUNCH(gemm_launch(GEMM_NN, EPI_BIAS_GELU, a, -1, st), "mlp-up product"); }
+    }
+    for (int j = 0; j < L.q; ++j) {  // F7
+      hipStream_t sj = as_stream(streams[(i + j * L.p) % ns]);
+      TRY(edge(st, sj));
+      {
+        ProfScope ps(PC_GEMM_DOWN, sj);
+        const size_t cj = (size_t)j * L.hq * 2;
+        GemmArgs a = gemm_args(act, L.fl, at(P->w_down, cj), L.h, at(mlp_partial, rh + cj), L.h, Ms, L.hq, L.fl);
+        LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "mlp-down piece");
+      }
+      TRY(edge(sj, st));
+    }
+    if (y) {  // F8
+      ProfScope ps(PC_RESID_OUT, st);
+      LAUNCH(residual_out_launch(x1, at(mlp_partial, rh), mlp_others ? at(mlp_others, rh) : nullptr, P->b_down,
+                                 at(y, rh), (long)Ms * L.h, L.h, st), "block output");
+    }
+  }
+  for (int k = 1; k < ns; ++k)
+    if (used[k]) TRY(edge(as_stream(streams[k]), s0));
+  return DOMINO_OK;
+}
+
+// ------------------------------------------------------------------------------------ backward
+int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* saved,
+                     const void* x, const void* dy,
+                     const void* dln2_others, const void* dln1_others,
+                     void* dln2_partial, void* dln1_partial, void* dx,
+                     const domino_grads* G, int accumulate,
+                     void* workspace, size_t workspace_bytes,
+                     void* const* streams, int nstreams) {
+  Layout L;
+  TRY(validate(cfg, &L));
+  TRY(check_params(L, P));
+  TRY(check_streams(streams, nstreams));
+  if (!saved || !x || !dy || !dln2_partial || !dln1_partial || !dx || !G)
+    return fail(DOMINO_ERR_NULL_POINTER, "saved, x, dy, dln2_partial, dln1_partial, dx or grads is NULL");
+  if (!G->norm1_g || !G->norm2_g || !G->w_qkv || !G->w_o || !G->w_up || !G->w_down)
+    return fail(DOMINO_ERR_NULL_POINTER, "a weight or norm-gain gradient pointer is NULL");
+  if (!L.llama && (!G->norm1_b || !G->norm2_b || !G->b_qkv || !G->b_o || !G->b_up || !G->b_down))
+    return fail(DOMINO_ERR_NULL_POINTER, "a GPT bias or norm-shift gradient pointer is NULL");
+  if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
+  if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
+  std::lock_guard<std::mutex> lock(g_mutex);
+  g_sync_used = 0;
+
+  const int ns = nstreams;
+  hipStream_t s0 = as_stream(streams[0]);
+  const int nused = L.p < ns ? L.p : ns;
+  for (int k = 1; k < nused; ++k) TRY(edge(s0, as_stream(streams[k])));
+
+  const int Ms = L.Ms;
+  const bool rms = L.llama;
+  void* ws = workspace;
+  hipStream_t prev = nullptr;     // stream of the previous slice: its weight gradients come first
+  hipEvent_t wg_prev[4] = {}, wg_cur[4] = {};
+  for (int i = 0; i < L.p; ++i) {
+    hipStream_t st = as_stream(streams[i % ns]);
+    const size_t r0 = (size_t)i * Ms;
+    const size_t rh = r0 * L.h * 2;
+    const char* xi = at(x, rh);
+    const char* dyi = at(dy, rh);
+    const char* ln1 = at(saved, L.ln1 + rh);
+    const char* qkv = at(saved, L.qkv + r0 * 3 * L.hl * 2);
+    const char* ctx = at(saved, L.ctx + r0 * L.hl * 2);
+    const float* lse = reinterpret_cast<const float*>(at(saved, L.lse)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
+    const char* x1 = at(saved, L.x1 + rh);
+    const char* ln2 = at(saved, L.ln2 + rh);
+    const char* pre = at(saved, L.pre + r0 * L.upc * 2);
+    const char* act = at(saved, L.act + r0 * L.fl * 2);
+    const float* mean1 = reinterpret_cast<const float*>(at(saved, L.mean1)) + r0;
+    const float* rstd1 = reinterpret_cast<const float*>(at(saved, L.rstd1)) + r0;
+    const float* mean2 = reinterpret_cast<const float*>(at(saved, L.mean2)) + r0;
+    const float* rstd2 = reinterpret_cast<const float*>(at(saved, L.rstd2)) + r0;
+    char* d_pre = at(ws, L.d_pre + r0 * L.upc * 2);
+    char* dx1 = at(ws, L.dx1 + rh);
+    char* dctx = at(ws, L.dctx + r0 * L.hl * 2);
+    char* dqkv = at(ws, L.dqkv + r0 * 3 * L.hl * 2);
+    float* dot = reinterpret_cast<float*>(at(ws, L.dot)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
+    float* red = reinterpret_cast<float*>(at(ws, L.red)) + (size_t)i * L.red_floats;
+    float* slots = reinterpret_cast<float*>(at(ws, L.slots)) + (size_t)i * NSLOTS * L.slot_floats;
+    auto slot = [&](int k) { return slots + (size_t)k * L.slot_floats; };
+    const int beta = (i > 0 || accumulate) ? 1 : 0;
+    const bool chain = prev && prev != st;      // weight gradients are summed over slices in slice order
+
+    auto wgrad = [&](int which, int cls, const void* A, long lda, const void* B, long ldb, float* C, long ldc,
+                     int M, int N) -> int {
+      if (chain) HIP_TRY(hipStreamWaitEvent(st, wg_prev[which], 0), "hipStreamWaitEvent");
+      {
+        ProfScope ps(cls, st);
+        GemmArgs a = gemm_args(A, lda, B, ldb, C, ldc, M, N, Ms);
+        a.beta = beta;
+        LAUNCH(gemm_launch(GEMM_TN, EPI_ACC_F32, a, -1, st), "weight gradient");
+      }
+      TRY(next_sync_event(&wg_cur[which]));
+      HIP_TRY(hipEventRecord(wg_cur[which], st), "hipEventRecord");
+      return DOMINO_OK;
+    };
+    auto colsum = [&](const void* g, long ld, int n, int k) -> int {
+      ProfScope ps(PC_COLSUM, st);
+      LAUNCH(colsum_partial_launch(g, ld, Ms, n, red, st), "bias gradient");
+      LAUNCH(colsum_finish_launch(red, COLSUM_PARTS, n, slot(k), 0, st), "bias gradient");
+      return DOMINO_OK;
+    };
+    auto norm_bwd = [&](const void* ga, const void* gb, const void* xin, const void* gamma, const float* mean,
+                        const float* rstd, const void* dres, void* out, int kg, int kb) -> int {
+      ProfScope ps(PC_NORM_BWD, st);
+      NormBwdArgs a{};
+      a.ga = ga; a.gb = gb; a.x = xin; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dres = dres; a.dx = out;
+      a.part_g = red; a.part_b = red + (size_t)norm_bwd_blocks(Ms) * L.h; a.rows = Ms; a.h = L.h; a.rms = rms;
+      LAUNCH(norm_bwd_launch(a, st), "norm backward");
+      LAUNCH(colsum_finish_launch(a.part_g, norm_bwd_blocks(Ms), L.h, slot(kg), 0, st), "norm gain gradient");
+      if (!rms) LAUNCH(colsum_finish_launch(a.part_b, norm_bwd_blocks(Ms), L.h, slot(kb), 0, st), "norm shift gradient");
+      return DOMINO_OK;
+    };
+
+    {  // B1 + B3: input gradient of the down-projection (all q column slices inside the K loop), activation backward fused
+      ProfScope ps(PC_DGRAD_DOWN, st);
+      GemmArgs a = gemm_args(dyi, L.h, P->w_down, L.h, d_pre, L.upc, Ms, L.fl, L.h);
+      a.aux = const_cast<char*>(pre); a.ldaux = L.upc; a.gelu_tanh = cfg->gelu_tanh;
+      if (L.llama) { a.n_split = L.fl; LAUNCH(gemm_launch(GEMM_NT, EPI_DSWIGLU, a, -1, st), "mlp-down input gradient"); }
+      else LAUNCH(gemm_launch(GEMM_NT, EPI_DGELU, a, -1, st), "mlp-down input gradient");
+    }
+    TRY(wgrad(0, PC_WGRAD_DOWN, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
+    if (!L.llama) TRY(colsum(dyi, L.h, L.h, SLOT_BDOWN));
+    {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
+      ProfScope ps(PC_DGRAD_UP, st);
+      GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(dln2_partial, rh), L.h, Ms, L.h, L.upc);
+      LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "mlp-up input gradient");
+    }
+    TRY(wgrad(1, PC_WGRAD_UP, ln2, L.h, d_pre, L.upc, G->w_up, L.upc, L.h, L.upc));
+    if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, SLOT_BUP));
+    // B5
+    TRY(norm_bwd(at(dln2_partial, rh), dln2_others ? at(dln2_others, rh) : nullptr, x1, P->norm2_g, mean2, rstd2,
+                 dyi, dx1, SLOT_G2, SLOT_B2));
+    {  // B6
+      ProfScope ps(PC_DGRAD_OUT, st);
+      GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
+      LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "out-projection input gradient");
+    }
+    TRY(wgrad(2, PC_WGRAD_OUT, ctx, L.hl, dx1, L.h, G->w_o, L.h, L.hl, L.h));
+    if (!L.llama) TRY(colsum(dx1, L.h, L.h, SLOT_BO));
+    {  // B7
+      ProfScope ps(PC_ATTN_BWD, st);
+      AttnArgs a{};
+      a.qkv = qkv; a.ld = 3 * L.hl; a.ctx = const_cast<char*>(ctx); a.ld_ctx = L.hl; a.dctx = dctx;
+      a.lse = const_cast<float*>(lse); a.dot = dot; a.dqkv = dqkv;
+      a.batch = L.b / L.p; a.seq = L.s; a.heads = L.nl; a.head_dim = L.d; a.scale = 1.0f / sqrtf((float)L.d);
+      LAUNCH(attention_bwd_launch(a, st), "attention backward");
+    }
+    if (L.llama) {
+      ProfScope ps(PC_ROPE, st);
+      LAUNCH(rope_launch(dqkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 1, st), "rotary embedding backward");
+    }
+    {  // B8: input gradient of QKV: the tensor the fourth all-reduce would sum
+      ProfScope ps(PC_DGRAD_QKV, st);
+      GemmArgs a = gemm_args(dqkv, 3 * L.hl, P->w_qkv, 3 * L.hl, at(dln1_partial, rh), L.h, Ms, L.h, 3 * L.hl);
+      LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "qkv input gradient");
+    }
+    TRY(wgrad(3, PC_WGRAD_QKV, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
+    if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, SLOT_BQKV));
+    TRY(norm_bwd(at(dln1_partial, rh), dln1_others ? at(dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
+                 dx1, at(dx, rh), SLOT_G1, SLOT_B1));
+
+    prev = st;
+    for (int k = 0; k < 4; ++k) wg_prev[k] = wg_cur[k];
+  }
+  for (int k = 1; k < nused; ++k) TRY(edge(as_stream(streams[k]), s0));
+
+  // vector gradients: sum the per-slice slots in slice order
+  {
+    ProfScope ps(PC_COLSUM, s0);
+    float* slots = reinterpret_cast<float*>(at(ws, L.slots));
+    const size_t stride = L.slot_floats;     // consecutive slots of one slice; slices NSLOTS*stride apart
+    struct { int k; float* out; int n; } vec[NSLOTS] = {
+      {SLOT_G1, G->norm1_g, L.h}, {SLOT_B1, G->norm1_b, L.h}, {SLOT_G2, G->norm2_g, L.h}, {SLOT_B2, G->norm2_b, L.h},
+      {SLOT_BQKV, G->b_qkv, 3 * L.hl}, {SLOT_BO, G->b_o, L.h}, {SLOT_BUP, G->b_up, L.fl}, {SLOT_BDOWN, G->b_down, L.h}};
+    for (auto& v : vec) {
+      if (!v.out) continue;
+      if (L.llama && v.k != SLOT_G1 && v.k != SLOT_G2) continue;
+      LAUNCH(colsum_finish_strided_launch(slots + (size_t)v.k * stride, L.p, NSLOTS * stride, v.n, v.out, accumulate, s0),
+             "vector gradient reduction");
+    }
+  }
+  return DOMINO_OK;
+}
+
+// ------------------------------------------------------------------------------------ single kernels
+int domino_gemm(int layout, int epilogue, int tile,
+                const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                int M, int N, int K, const void* bias, void* aux, int64_t ldaux,
+                int n_split, int beta, int gelu_tanh, void* stream) {
+  if (!A || !B || !C) return fail(DOMINO_ERR_NULL_POINTER, "A, B or C is NULL");
+  if (M <= 0 || N <= 0 || K <= 0) return fail(DOMINO_ERR_INVALID_ARG, "M, N, K must be positive");
+  if (M % 8 || N % 8 || K % 8 || lda % 8 || ldb % 8 || ldc % 4) return fail(DOMINO_ERR_UNSUPPORTED, "dimensions must be multiples of 8");
+  if (tile < -1 || tile > 2) return fail(DOMINO_ERR_INVALID_ARG, "tile %d outside [-1, 2]", tile);
+  const bool ok = (layout == DOMINO_GEMM_NN && (epilogue == DOMINO_EPI_STORE || epilogue == DOMINO_EPI_BIAS_GELU || epilogue == DOMINO_EPI_SWIGLU)) ||
+                  (layout == DOMINO_GEMM_NT && (epilogue == DOMINO_EPI_STORE || epilogue == DOMINO_EPI_DGELU || epilogue == DOMINO_EPI_DSWIGLU)) ||
+                  (layout == DOMINO_GEMM_TN && epilogue == DOMINO_EPI_ACC_F32);
+  if (!ok) return fail(DOMINO_ERR_INVALID_ARG, "epilogue %d is not defined for layout %d", epilogue, layout);
+  const bool needs_aux = epilogue == DOMINO_EPI_BIAS_GELU || epilogue == DOMINO_EPI_SWIGLU || epilogue == DOMINO_EPI_DGELU || epilogue == DOMINO_EPI_DSWIGLU;
+  if (needs_aux && !aux) return fail(DOMINO_ERR_NULL_POINTER, "this epilogue needs aux");
+  if (needs_aux && ldaux % 8) return fail(DOMINO_ERR_UNSUPPORTED, "ldaux must be a multiple of 8");
+  if (epilogue == DOMINO_EPI_SWIGLU || epilogue == DOMINO_EPI_DSWIGLU) {
+    if (n_split != N) return fail(DOMINO_ERR_INVALID_ARG, "SwiGLU epilogues need n_split == N");
+    if (epilogue == DOMINO_EPI_SWIGLU && n_split % 32) return fail(DOMINO_ERR_UNSUPPORTED, "n_split must be a multiple of 32");
+  }
+  GemmArgs a = gemm_args(A, lda, B, ldb, C, ldc, M, N, K);
+  a.bias = bias; a.aux = aux; a.ldaux = ldaux; a.n_split = n_split; a.beta = beta; a.gelu_tanh = gelu_tanh;
+  const long wide_b = (layout == DOMINO_GEMM_NT) ? ((long)(N - 1) * ldb + K) : ((long)(K - 1) * ldb + (epilogue == DOMINO_EPI_SWIGLU ? 2L * N : N));
+  const long wide_a = (layout == DOMINO_GEMM_TN) ? ((long)(K - 1) * lda + M) : ((long)(M - 1) * lda + K);
+  if (wide_a * 2 >= TWO_GIB || wide_b * 2 >= TWO_GIB) return fail(DOMINO_ERR_UNSUPPORTED, "an operand would reach 2 GiB");
+  HIP_TRY(gemm_launch(layout, epilogue, a, tile, as_stream(stream)), "gemm launch");
+  return DOMINO_OK;
+}
+
+int domino_norm_fwd(const void* x, const void* add1, const void* add2, const void* vec,
+                    const void* gamma, const void* beta, void* xsum, void* y, float* mean, float* rstd,
+                    int rows, int h, int rms, float eps, void* stream) {
+  if (!x || !gamma || !y || !rstd) return fail(DOMINO_ERR_NULL_POINTER, "x, gamma, y or rstd is NULL");
+  if (rows <= 0 || h <= 0) return fail(DOMINO_ERR_INVALID_ARG, "rows and h must be positive");
+  if (h % 8 || h > 8192) return fail(DOMINO_ERR_UNSUPPORTED, "h must be a multiple of 8 and at most 8192");
+  NormFwdArgs a{};
+  a.x = x; a.add1 = add1; a.add2 = add2; a.vec = vec; a.gamma = gamma; a.beta = beta; a.xsum = xsum; a.y = y;
+  a.mean = rms ? nullptr : mean; a.rstd = rstd; a.rows = rows; a.h = h; a.rms = rms; a.eps = eps;
+  HIP_TRY(norm_fwd_launch(a, as_stream(stream)), "norm forward launch");
+  return DOMINO_OK;
+}
+
+size_t domino_norm_bwd_scratch_floats(int rows, int h) {
+  if (rows <= 0 || h <= 0) return 0;
+  return 2 * (size_t)norm_bwd_blocks(rows) * h;
+}
+
+int domino_norm_bwd(const void* ga, const void* gb, const void* x, const void* gamma,
+                    const float* mean, const float* rstd, const void* dres, void* dx,
+                    float* dgamma, float* dbeta, float* scratch,
+                    int rows, int h, int rms, void* stream) {
+  if (!ga || !x || !gamma || !rstd || !dx || !dgamma || !scratch) return fail(DOMINO_ERR_NULL_POINTER, "a required pointer is NULL");
+  if (!rms && (!mean || !dbeta)) return fail(DOMINO_ERR_NULL_POINTER, "LayerNorm needs mean and dbeta");
+  if (rows <= 0 || h <= 0) return fail(DOMINO_ERR_INVALID_ARG, "rows and h must be positive");
+  if (h % 8 || h > 8192) return fail(DOMINO_ERR_UNSUPPORTED, "h must be a multiple of 8 and at most 8192");
+  NormBwdArgs a{};
+  a.ga = ga; a.gb = gb; a.x = x; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dres = dres; a.dx = dx;
+  const int nb = norm_bwd_blocks(rows);
+  a.part_g = scratch; a.part_b = scratch + (size_t)nb * h; a.rows = rows; a.h = h; a.rms = rms;
+  hipStream_t st = as_stream(stream);
+  HIP_TRY(norm_bwd_launch(a, st), "norm backward launch");
+  HIP_TRY(colsum_finish_launch(a.part_g, nb, h, dgamma, 0, st), "norm gain gradient");
+  if (!rms) HIP_TRY(colsum_finish_launch(a.part_b, nb, h, dbeta, 0, st), "norm shift gradient");
+  return DOMINO_OK;
+}
+
+static int check_attn(int64_t ld, int batch, int seq, int heads, int head_dim) {
+  if (batch <= 0 || seq <= 0 || heads <= 0) return fail(DOMINO_ERR_INVALID_ARG, "batch, seq, heads must be positive");
+  if (head_dim != 64 && head_dim != 80 && head_dim != 128) return fail(DOMINO_ERR_UNSUPPORTED, "head_dim %d not in {64, 80, 128}", head_dim);
+  if (ld < 3L * heads * head_dim || ld % 8) return fail(DOMINO_ERR_INVALID_ARG, "ld must be a multiple of 8 and at least 3*heads*head_dim");
+  if ((long)batch * seq * ld * 2 >= TWO_GIB) return fail(DOMINO_ERR_UNSUPPORTED, "qkv would reach 2 GiB");
+  return DOMINO_OK;
+}
+
+int domino_attention_fwd(const void* qkv, int64_t ld, int batch, int seq, int heads, int head_dim,
+                         void* ctx, float* lse, void* stream) {
+  if (!qkv || !ctx || !lse) return fail(DOMINO_ERR_NULL_POINTER, "qkv, ctx or lse is NULL");
+  TRY(check_attn(ld, batch, seq, heads, head_dim));
+  AttnArgs a{};
+  a.qkv = qkv; a.ld = ld; a.ctx = ctx; a.ld_ctx = (long)heads * head_dim; a.lse = lse;
+  a.batch = batch; a.seq = seq; a.heads = heads; a.head_dim = head_dim; a.scale = 1.0f / sqrtf((float)head_dim);
+  HIP_TRY(attention_fwd_launch(a, as_stream(stream)), "attention forward launch");
+  return DOMINO_OK;
+}
+
+int domino_attention_bwd(const void* qkv, int64_t ld, const void* ctx, const void* dctx, const float* lse,
+                         void* dqkv, float* dot, int batch, int seq, int heads, int head_dim, void* stream) {
+  if (!qkv || !ctx || !dctx || !lse || !dqkv || !dot) return fail(DOMINO_ERR_NULL_POINTER, "a required pointer is NULL");
+  TRY(check_attn(ld, batch, seq, heads, head_dim));
+  AttnArgs a{};
+  a.qkv = qkv; a.ld = ld; a.ctx = const_cast<void*>(ctx); a.ld_ctx = (long)heads * head_dim; a.dctx = dctx;
+  a.lse = const_cast<float*>(lse); a.dot = dot; a.dqkv = dqkv;
+  a.batch = batch; a.seq = seq; a.heads = heads; a.head_dim = head_dim; a.scale = 1.0f / sqrtf((float)head_dim);
+  HIP_TRY(attention_bwd_launch(a, as_stream(stream)), "attention backward launch");
+  return DOMINO_OK;
+}
+
+int domino_rope(void* m, int64_t ld, int rows, int seq, int col0, int nblocks, int heads, int head_dim,
+                float base, int inverse, void* stream) {
+  if (!m) return fail(DOMINO_ERR_NULL_POINTER, "m is NULL");
+  if (rows <= 0 || seq <= 0 || nblocks <= 0 || heads <= 0 || head_dim <= 0 || head_dim % 2 || col0 < 0)
+    return fail(DOMINO_ERR_INVALID_ARG, "rows, seq, nblocks, heads must be positive and head_dim even");
+  if (col0 + (long)nblocks * heads * head_dim > ld) return fail(DOMINO_ERR_INVALID_ARG, "column blocks exceed ld");
+  if (!(base > 1.0f)) return fail(DOMINO_ERR_INVALID_ARG, "base must exceed 1");
+  HIP_TRY(rope_launch(m, ld, rows, seq, col0, nblocks, heads, head_dim, base, inverse, as_stream(stream)), "rope launch");
+  return DOMINO_OK;
+}
+
+int domino_colsum(const void* g, int64_t ld, int rows, int n, float* out, int accumulate, float* scratch, void* stream) {
+  if (!g || !out || !scratch) return fail(DOMINO_ERR_NULL_POINTER, "g, out or scratch is NULL");
+  if (rows <= 0 || n <= 0) return fail(DOMINO_ERR_INVALID_ARG, "rows and n must be positive");
+  if (n % 8 || ld % 8 || ld < n) return fail(DOMINO_ERR_UNSUPPORTED, "n and ld must be multiples of 8, ld >= n");
+  hipStream_t st = as_stream(stream);
+  HIP_TRY(colsum_partial_launch(g, ld, rows, n, scratch, st), "colsum launch");
+  HIP_TRY(colsum_finish_launch(scratch, COLSUM_PARTS, n, out, accumulate, st), "colsum launch");
+  return DOMINO_OK;
+}
+
+// ------------------------------------------------------------------------------------ instrumentation
+int domino_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_mutex);
+  g_prof_on = on != 0;
+  return DOMINO_OK;
+}
+int domino_profile_classes(void) { return PC_COUNT; }
+const char* domino_profile_name(int cls) { return (cls >= 0 && cls < PC_COUNT) ? PROF_NAMES[cls] : ""; }
+
+int domino_profile_read(int cls, double* total_ms, int* launches) {
+  if (cls < 0 || cls >= PC_COUNT) return fail(DOMINO_ERR_INVALID_ARG, "class %d outside [0, %d)", cls, (int)PC_COUNT);
+  if (!total_ms || !launches) return fail(DOMINO_ERR_NULL_POINTER, "total_ms or launches is NULL");
+  std::lock_guard<std::mutex> lock(g_mutex);
+  double tot = 0.0;
+  int n = 0;
+  for (auto& r : g_prof_recs) {
+    if (r.cls != cls) continue;
+    HIP_TRY(hipEventSynchronize(r.stop), "hipEventSynchronize");
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.start, r.stop), "hipEventElapsedTime");
+    tot += ms;
+    ++n;
+  }
+  *total_ms = tot;
+  *launches = n;
+  return DOMINO_OK;
+}
+
+int domino_profile_reset(void) {
+  std::lock_guard<std::mutex> lock(g_mutex);
+  for (auto& r : g_prof_recs) { g_prof_free.push_back(r.start); g_prof_free.push_back(r.stop); }
+  g_prof_recs.clear();
+  return DOMINO_OK;
+}
+
+void domino_shutdown(void) {
+  std::lock_guard<std::mutex> lock(g_mutex);
+  for (auto e : g_sync_events) (void)hipEventDestroy(e);
+  g_sync_events.clear();
+  g_sync_used = 0;
+  for (auto& r : g_prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  g_prof_recs.clear();
+  for (auto e : g_prof_free) (void)hipEventDestroy(e);
+  g_prof_free.clear();
+}
+
+}  // extern "C"

@@ -39,5 +39,7 @@ hipError_t norm_fwd_launch(const NormFwdArgs& a, hipStream_t st);
 hipError_t norm_bwd_launch(const NormBwdArgs& a, hipStream_t st);
 // out[n] (+)= sum over nparts rows of part[nparts][n], summed in index order
 hipError_t colsum_finish_launch(const float* part, int nparts, int n, float* out, int accumulate, hipStream_t st);
+// same with the partial rows `stride` floats apart
+hipError_t colsum_finish_strided_launch(const float* part, int nparts, long stride, int n, float* out, int accumulate, hipStream_t st);
 // part[COLSUM_PARTS][n] = partial column sums of the bf16 matrix g[rows][ld]
 hipError_t colsum_partial_launch(const void* g, long ld, int rows, int n, float* part, hipStream_t st);

@@ -238,11 +238,11 @@ void norm_bwd_kernel(const NormBwdArgs p) {
 
 // out[col] (+)= sum_k part[k][col], k in fixed order: the second stage of every column reduction.
 __global__ __launch_bounds__(256)
-void colsum_finish_kernel(const float* __restrict__ part, int nparts, int n, float* __restrict__ out, int accumulate) {
+void colsum_finish_kernel(const float* __restrict__ part, int nparts, long stride, int n, float* __restrict__ out, int accumulate) {
   const int col = blockIdx.x * 256 + threadIdx.x;
   if (col >= n) return;
   float s = 0.0f;
-  for (int k = 0; k < nparts; ++k) s += part[(long)k * n + col];
+  for (int k = 0; k < nparts; ++k) s += part[(long)k * stride + col];
   out[col] = accumulate ? out[col] + s : s;
 }
 
@@ -317,7 +317,11 @@ hipError_t norm_bwd_launch(const NormBwdArgs& a, hipStream_t st) {
 }
 
 hipError_t colsum_finish_launch(const float* part, int nparts, int n, float* out, int accumulate, hipStream_t st) {
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, st, part, nparts, n, out, accumulate);
+  return colsum_finish_strided_launch(part, nparts, n, n, out, accumulate, st);
+}
+
+hipError_t colsum_finish_strided_launch(const float* part, int nparts, long stride, int n, float* out, int accumulate, hipStream_t st) {
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, st, part, nparts, stride, n, out, accumulate);
   return hipGetLastError();
 }
 

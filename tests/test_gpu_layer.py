@@ -1,0 +1,175 @@
+"""Layer parity: domino_layer_fwd / domino_layer_bwd through the C ABI against the fp64 oracle, on the
+same seeded inputs, for every output and every gradient tensor.  Bar (from the benchmark spec):
+max|err| <= 2e-2 * max|ref| per tensor, at every p x q slicing."""
+import numpy as np
+import pytest
+
+from oracle import domino_oracle as O
+from paper_2409_15241_amd import synth
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2409_15241_amd import domino, harness
+    domino.load()
+    return harness
+
+
+def f64(d):
+    return {k: (None if v is None else v.astype(np.float64)) for k, v in d.items()}
+
+
+def relerr(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def run_gpu(H, sc, params, x, dy, others, nstreams=4, accumulate_twice=False):
+    buf = H.LayerBuffers(sc, params, x, dy, others, nstreams=nstreams)
+    buf.forward()
+    buf.backward(accumulate=False)
+    if accumulate_twice:
+        buf.backward(accumulate=True)
+    buf.sync()
+    out = {k: H.to_host_f64(getattr(buf, k)) for k in
+           ("attn_partial", "mlp_partial", "y", "dln2_partial", "dln1_partial", "dx")}
+    out["grads"] = {k: (None if g is None else g.cpu().numpy().astype(np.float64)) for k, g in buf.grads.items()}
+    shp = (sc.batch, sc.seq)
+    out["x1"] = H.to_host_f64(buf.saved_tensor("x1")).reshape(*shp, sc.hidden)
+    out["ctx"] = H.to_host_f64(buf.saved_tensor("ctx")).reshape(*shp, sc.h_local)
+    out["lse"] = buf.saved_tensor("lse").cpu().numpy().astype(np.float64).reshape(sc.batch, sc.local_heads, sc.seq)
+    return out
+
+
+def oracle(sc, params, x, dy, others):
+    P = f64(params)
+    oth = f64(others) if others else {}
+    F = O.rank_layer_fwd(sc, P, x.astype(np.float64), oth.get("attn_others"), oth.get("mlp_others"))
+    B = O.rank_layer_bwd(sc, P, F, dy.astype(np.float64), oth.get("dln2_others"), oth.get("dln1_others"))
+    return F, B
+
+
+def check(got, F, B, tol=TOL, grad_scale=1.0):
+    worst = {}
+    for k in ("attn_partial", "mlp_partial", "y", "x1", "ctx"):
+        worst[k] = relerr(got[k], F[k])
+    assert np.max(np.abs(got["lse"] - F["lse"])) < 2e-2
+    for k in ("dln2_partial", "dln1_partial", "dx"):
+        worst[k] = relerr(got[k], B[k])
+    for k, g in B["grads"].items():
+        if g is None:
+            assert got["grads"][k] is None
+        else:
+            worst["d" + k] = relerr(got["grads"][k], grad_scale * g)
+    bad = {k: v for k, v in worst.items() if not v <= tol}
+    assert not bad, f"over tolerance: {bad}\nall: {worst}"
+    return worst
+
+
+def case(H, sc, random_affine=False, with_others=True, nstreams=4):
+    params = synth.make_rank_params(sc, random_affine=random_affine)
+    x, dy = synth.make_activations(sc)
+    others = synth.make_others(sc) if with_others else None
+    got = run_gpu(H, sc, params, x, dy, others, nstreams)
+    F, B = oracle(sc, params, x, dy, others)
+    return check(got, F, B)
+
+
+TINY = synth.WORKLOADS["tiny"]
+TINYL = synth.WORKLOADS["tiny-llama"]
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (1, 4), (2, 4), (4, 1), (4, 2), (4, 4)])
+def test_tiny_every_slicing(H, base, p, q):
+    sc = base.replace(p=p, q=q, batch=4 if p == 4 else base.batch)
+    case(H, sc, random_affine=True)
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+def test_tiny_as_configured_zero_biases_no_others(H, base):
+    case(H, base, random_affine=False, with_others=False)
+
+
+@pytest.mark.parametrize("rank", [0, 1])
+def test_tiny_other_rank_and_erf_gelu(H, rank):
+    case(H, TINY.replace(rank=rank, gelu_tanh=0), random_affine=True)
+
+
+def test_ranks_sum_to_the_unsharded_layer(H):
+    """The library is called once per rank on the same GPU; with the true 'others' (from the oracle's
+    simulated all-reduces) each rank's y equals the full layer's, and the partials sum to the
+    unsharded sub-layer outputs (Eq. 1)."""
+    sc = TINY
+    shards = [synth.make_rank_params(sc, r, random_affine=True) for r in range(sc.tp)]
+    x, dy = synth.make_activations(sc)
+    fwd, bwd = O.simulate_tp(sc, [f64(s) for s in shards], x.astype(np.float64), dy.astype(np.float64))
+    full = O.full_from_shards([f64(s) for s in shards], sc)
+    Ff = O.full_layer_fwd(sc, full, x.astype(np.float64))
+    Bf = O.full_layer_bwd(sc, full, Ff, dy.astype(np.float64))
+    rb = synth.round_bf16
+    attn_sum, mlp_sum, d2_sum, d1_sum = 0, 0, 0, 0
+    for r in range(sc.tp):
+        others = {
+            "attn_others": rb((Ff["attn_partial"] - fwd[r]["attn_partial"]).astype(np.float32)),
+            "mlp_others": rb((Ff["mlp_partial"] - fwd[r]["mlp_partial"]).astype(np.float32)),
+            "dln2_others": rb((Bf["dln2_partial"] - bwd[r]["dln2_partial"]).astype(np.float32)),
+            "dln1_others": rb((Bf["dln1_partial"] - bwd[r]["dln1_partial"]).astype(np.float32)),
+        }
+        got = run_gpu(H, sc.replace(rank=r), shards[r], x, dy, others)
+        assert relerr(got["y"], Ff["y"]) < TOL
+        assert relerr(got["dx"], Bf["dx"]) < TOL
+        attn_sum = attn_sum + got["attn_partial"]; mlp_sum = mlp_sum + got["mlp_partial"]
+        d2_sum = d2_sum + got["dln2_partial"]; d1_sum = d1_sum + got["dln1_partial"]
+    assert relerr(attn_sum, Ff["attn_partial"]) < TOL
+    assert relerr(mlp_sum, Ff["mlp_partial"]) < TOL
+    assert relerr(d2_sum, Bf["dln2_partial"]) < TOL
+    assert relerr(d1_sum, Bf["dln1_partial"]) < TOL
+
+
+MID = [
+    # head_dim 80, out-projection K = 320, sequence not a multiple of the 128-query block
+    synth.ShardConfig("mid-gpt-d80", 640, 8, 2, 1, 2, 2, 2, 328, 2560, synth.ARCH_GPT, index=11),
+    # head_dim 128, SwiGLU width 43*32 = 1376 (K tail of half a tile), q = 4
+    synth.ShardConfig("mid-llama", 1024, 8, 4, 2, 1, 4, 2, 200, 5504, synth.ARCH_LLAMA, index=12),
+    # head_dim 64 with a 256x256-tile sized problem
+    synth.ShardConfig("mid-gpt-d64", 1024, 16, 2, 0, 2, 1, 4, 256, 4096, synth.ARCH_GPT, index=13),
+]
+
+
+@pytest.mark.parametrize("sc", MID, ids=[m.name for m in MID])
+def test_mid_shapes_with_ragged_tiles(H, sc):
+    case(H, sc, random_affine=True)
+
+
+def test_schedule_invariance_bitwise(H):
+    """The same call on 1 stream and on 4 streams: identical bits (accumulation order is fixed)."""
+    sc = TINY.replace(batch=4, p=4, q=2)
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    others = synth.make_others(sc)
+    a = run_gpu(H, sc, params, x, dy, others, nstreams=1)
+    b = run_gpu(H, sc, params, x, dy, others, nstreams=4)
+    c = run_gpu(H, sc, params, x, dy, others, nstreams=8)
+    for k in ("attn_partial", "mlp_partial", "y", "dln2_partial", "dln1_partial", "dx"):
+        np.testing.assert_array_equal(a[k], b[k], err_msg=k)
+        np.testing.assert_array_equal(a[k], c[k], err_msg=k)
+    for k, g in a["grads"].items():
+        if g is not None:
+            np.testing.assert_array_equal(g, b["grads"][k], err_msg=k)
+            np.testing.assert_array_equal(g, c["grads"][k], err_msg=k)
+
+
+def test_accumulate_adds_to_existing_gradients(H):
+    sc = TINY
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    got = run_gpu(H, sc, params, x, dy, None, accumulate_twice=True)
+    F, B = oracle(sc, params, x, dy, None)
+    check(got, F, B, grad_scale=2.0)
