@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the rank-local Domino layer (forward + backward) on one MI355X.
+
+A step is one pass of the whole hot path: domino_layer_fwd + domino_layer_bwd over one batch of
+synthetic input (all p x q pieces, all streams joined), inputs resident in HBM.  Prints ONE JSON line:
+whole-job throughput in algorithmic TFLOP/s (causal attention counted at half the dense s^2,
+backward = 2 x forward, no recomputation counted), the roofline of the dominant kernel measured with
+HIP events on the kernel's own stream, and the fp64 CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gpt3-13b] [--streams 4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+DEFAULT_WORKLOAD = "gpt3-13b"      # the shard the throughput target is quoted on
+
+
+def gemm_flops_per_launch(sc):
+    """Algorithmic flops of one launch of each GEMM step class (one row slice; one column piece for
+    the two row-parallel products)."""
+    Ms = sc.tokens // sc.p
+    h, hl, fl, upc, hq = sc.hidden, sc.h_local, sc.f_local, sc.up_cols, sc.hidden // sc.q
+    return {
+        "gemm_qkv": 2.0 * Ms * h * 3 * hl, "gemm_out": 2.0 * Ms * hl * hq, "gemm_up": 2.0 * Ms * h * upc,
+        "gemm_down": 2.0 * Ms * fl * hq, "dgrad_down": 2.0 * Ms * h * fl, "wgrad_down": 2.0 * Ms * fl * h,
+        "dgrad_up": 2.0 * Ms * upc * h, "wgrad_up": 2.0 * Ms * h * upc, "dgrad_out": 2.0 * Ms * h * hl,
+        "wgrad_out": 2.0 * Ms * hl * h, "dgrad_qkv": 2.0 * Ms * 3 * hl * h, "wgrad_qkv": 2.0 * Ms * h * 3 * hl,
+    }
+
+
+def algorithmic_flops(sc):
+    M = sc.tokens
+    gemm = 2.0 * M * (sc.hidden * 3 * sc.h_local + sc.h_local * sc.hidden + sc.hidden * sc.up_cols
+                      + sc.f_local * sc.hidden)
+    attn = 2.0 * sc.batch * sc.local_heads * sc.seq * sc.seq * sc.head_dim
+    return 3.0 * (gemm + attn)
+
+
+def cpu_baseline(sc, budget_s=30.0):
+    """The oracle as it stands, on the host cores, on one row slice of the same workload."""
+    import numpy as np
+    from oracle import domino_oracle as O
+    from paper_2409_15241_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    sub = sc.replace(batch=sc.batch // sc.p, p=1, q=1)          # one row slice: b/p batch elements
+    params = {k: (None if v is None else v.astype(np.float64)) for k, v in synth.make_rank_params(sc).items()}
+    x, dy = synth.make_activations(sc)
+    x, dy = x[:sub.batch].astype(np.float64), dy[:sub.batch].astype(np.float64)
+    t0 = time.perf_counter()
+    F = O.rank_layer_fwd(sub, params, x)
+    O.rank_layer_bwd(sub, params, F, dy)
+    dt = time.perf_counter() - t0
+    flops = algorithmic_flops(sub)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one row slice ({sub.batch} of {sc.batch} batch elements, {sub.tokens} tokens) "
+                      f"fwd+bwd in fp64, {dt:.1f} s, within a {budget_s:.0f} s budget"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--p", type=int, default=None)
+    ap.add_argument("--q", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-step-class timing table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is the one-GPU rank-local path; run it with --gpus 1 "
+              "(the tensor-parallel all-reduce across GPUs is outside its scope)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2409_15241_amd import domino, harness, synth
+    domino.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    sc = synth.WORKLOADS[args.workload]
+    if args.p or args.q:
+        sc = sc.replace(p=args.p or sc.p, q=args.q or sc.q)
+    params = synth.make_rank_params(sc)
+    x, dy = synth.make_activations(sc)
+    others = synth.make_others(sc)
+    buf = harness.LayerBuffers(sc, params, x, dy, others, nstreams=args.streams)
+    s0 = buf.streams[0]
+
+    def step():
+        buf.forward()
+        buf.backward(accumulate=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = wall * 1e3 / args.steps
+    flops = algorithmic_flops(sc)
+    value = flops / (ms * 1e-3) / 1e12
+
+    # forward-only / backward-only, event-timed on streams[0] (where the library joins its streams)
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(s0)
+        for _ in range(n):
+            fn()
+        e1.record(s0)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    fwd_ms = timed(buf.forward, max(3, args.steps // 3))
+    bwd_ms = timed(lambda: buf.backward(False), max(3, args.steps // 3))
+
+    roofline = None
+    if not args.no_roofline:
+        # the same K steps again with every launch bracketed by timing events on its own stream
+        domino.domino_profile_reset()
+        domino.domino_profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        inst_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        domino.domino_profile_enable(False)
+        per = gemm_flops_per_launch(sc)
+        table = {}
+        for c in range(domino.domino_profile_classes()):
+            tot, n = domino.domino_profile_read(c)
+            if n:
+                table[domino.domino_profile_name(c)] = (tot, n)
+        domino.domino_profile_reset()
+        gemms = {k: v for k, v in table.items() if k in per}
+        dom_name = max(gemms, key=lambda k: gemms[k][0])
+        tot, n = gemms[dom_name]
+        avg_ms = tot / n
+        achieved = per[dom_name] / (avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                    "avg_launch_us": avg_ms * 1e3, "launches_per_step": n // args.steps,
+                    "flops_per_launch": per[dom_name], "ms_per_step_instrumented": inst_ms}
+        if args.breakdown:
+            print(f"{'class':14s} {'launch/step':>11s} {'us/launch':>10s} {'ms/step':>8s} {'TFLOP/s':>8s}", file=sys.stderr)
+            for k, (t, m) in sorted(table.items(), key=lambda kv: -kv[1][0]):
+                tf = per[k] / (t / m * 1e-3) / 1e12 if k in per else float("nan")
+                print(f"{k:14s} {m // args.steps:11d} {t / m * 1e3:10.1f} {t / args.steps:8.3f} {tf:8.1f}", file=sys.stderr)
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(sc)
+
+    line = {
+        "metric": "layer fwd+bwd TFLOP/s per rank shard (1 MI355X); % of bf16 MFMA peak",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": sc.name, "hidden": sc.hidden, "heads": sc.heads, "tp": sc.tp, "rank": sc.rank,
+                   "batch": sc.batch, "seq": sc.seq, "ffn": sc.ffn, "p": sc.p, "q": sc.q,
+                   "arch": "llama" if sc.arch else "gpt", "streams": args.streams},
+        "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
+        "algorithmic_gflop_per_step": flops / 1e9, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

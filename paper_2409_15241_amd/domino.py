@@ -62,6 +62,10 @@ def load() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2409_15241_amd.build`")
+    # The caller's device memory and streams come from torch, which ships its own HIP runtime under
+    # the same soname: load torch first so that the library binds to that one runtime instead of
+    # bringing a second copy into the process (handles from one are invalid in the other).
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, f32, sz = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_size_t
     cfgp = C.POINTER(domino_cfg)
