@@ -4,40 +4,42 @@
 //   C[m][n] = epilogue( sum_k Aop(m,k) * Bop(k,n) ),  fp32 accumulation in MFMA 32x32x16.
 //
 // Each operand is either contraction-contiguous in memory (KC: [row][k]) or contraction-strided
-// (KS: [k][row]); see lds_tile.h.  The three products of a linear layer map to
+// (KS: [k][row]); see lds_dma.h.  The three products of a linear layer map to
 //   forward   X[M,K]   * W[K,N]            : A KC, B KS
 //   dgrad     dY[M,N'] * W[K',N']^T        : A KC, B KC   (contraction over N')
 //   wgrad     X[M',K']^T * dY[M',N]        : A KS, B KS   (contraction over the tokens M')
 //
 // Work decomposition: one workgroup per BM x BN tile of C, (BM/WM)*(BN/WN) waves, each owning a
-// WM x WN sub-tile as (WN/32) x (WM/32) MFMA accumulators.  Operand tiles of 64 contraction
-// elements are double-buffered in LDS: the next tile's global loads are issued before the MFMA
-// loop of the current one and written to the other buffer after it (one barrier per step).
+// WM x WN sub-tile as (WN/32) x (WM/32) MFMA accumulators.  Operand tiles of 32 contraction elements
+// travel HBM/L2 -> LDS with buffer_load ... lds through a ring of NST stages: while the MFMAs consume
+// stage kt, the loads of tiles kt+1 .. kt+NST-1 are in flight.  One s_waitcnt vmcnt + one barrier per
+// tile; no VGPR staging, no ds_write.
 // The MFMA is issued with the roles swapped (first operand = B fragment) so that a lane ends up
 // with 4 consecutive n for one m: 8-byte bf16 / 16-byte fp32 stores.
 #include "gemm.h"
-#include "lds_tile.h"
+#include "lds_dma.h"
 
 namespace {
+
+constexpr int NST = 4;   // LDS ring depth
 
 template <int BM, int BN, int WM, int WN, bool AKS, bool BKS, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64)
 void gemm_kernel(const GemmArgs p) {
-  constexpr int NT = (BM / WM) * (BN / WN) * 64;
+  constexpr int NW = (BM / WM) * (BN / WN);
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int A_BYTES = BM * TILE_ROW_BYTES, B_BYTES = BN * TILE_ROW_BYTES;
+  constexpr int A_BYTES = BM * DMA_BK * 2, B_BYTES = BN * DMA_BK * 2;
   constexpr int STAGE = A_BYTES + B_BYTES;
-  extern __shared__ __align__(16) uint8_t smem[];
+  extern __shared__ __align__(1024) uint8_t smem[];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wave % (BM / WM)) * WM, wn0 = (wave / (BM / WM)) * WN;
 
-  // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give every XCD a
-  // contiguous run of tiles (they share operand tiles through that XCD's L2).
-  const int per_xcd = (p.tiles_m * p.tiles_n + 7) >> 3;
-  const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (tile >= p.tiles_m * p.tiles_n) return;
+  // Consecutive workgroup ids land on different XCDs (each with its own L2): with m fastest, the
+  // tiles of one XCD share few A panels and walk the B panels in step.
+  const int tile = blockIdx.x;
   const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
   const int m0 = tm * BM, n0 = tn * BN;
 
@@ -55,21 +57,22 @@ void gemm_kernel(const GemmArgs p) {
     }
   };
 
-  typename std::conditional<AKS, MoverKS<BM, NT>, MoverKC<BM, NT>>::type mvA;
-  typename std::conditional<BKS, MoverKS<BN, NT>, MoverKC<BN, NT>>::type mvB;
-
-  if constexpr (AKS) mvA.init((int)p.lda, IdentityCols{m0, p.M}, tid);
-  else mvA.init((int)p.lda, m0, p.M, tid);
+  DmaLoader<BM, NW, AKS> ldA;
+  DmaLoader<BN, NW, BKS> ldB;
+  if constexpr (AKS) ldA.init_ks((int)p.lda, IdentityCols{m0, p.M}, wave, lane);
+  else ldA.init_kc((int)p.lda, m0, p.M, wave, lane);
   if constexpr (BKS) {
-    if constexpr (EPI == EPI_SWIGLU) mvB.init((int)p.ldb, GluCols{tn * (BN / 2), p.n_split}, tid);
-    else mvB.init((int)p.ldb, IdentityCols{n0, p.N}, tid);
+    if constexpr (EPI == EPI_SWIGLU) ldB.init_ks((int)p.ldb, GluCols{tn * (BN / 2), p.n_split}, wave, lane);
+    else ldB.init_ks((int)p.ldb, IdentityCols{n0, p.N}, wave, lane);
   } else {
-    mvB.init((int)p.ldb, n0, p.N, tid);
+    ldB.init_kc((int)p.ldb, n0, p.N, wave, lane);
   }
-  auto load_tiles = [&](int k0) {
-    mvA.load(A, k0, p.K);
-    mvB.load(B, k0, p.K);
+  auto issue_tile = [&](int t) {          // tiles past the end read out of bounds and store zeros
+    uint8_t* st = smem + (t % NST) * STAGE;
+    ldA.issue(A, st, t * DMA_BK, p.K, wave);
+    ldB.issue(B, st + A_BYTES, t * DMA_BK, p.K, wave);
   };
+  constexpr int LOADS_PER_TILE = DmaLoader<BM, NW, AKS>::IPW + DmaLoader<BN, NW, BKS>::IPW;
 
   f32x16 acc[TN][TM];
 #pragma unroll
@@ -79,37 +82,80 @@ void gemm_kernel(const GemmArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const int nk = (p.K + TILE_K - 1) / TILE_K;
-  load_tiles(0);
-  mvA.store(smem, tid);
-  mvB.store(smem + A_BYTES, tid);
-  __syncthreads();
+  // per-lane LDS byte offsets of the fragments inside a stage, for the two 16-deep MFMA steps of a tile
+  uint32_t offA[2][AKS ? TM : 1], offB[2][BKS ? TN : 1];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    if constexpr (AKS) {
+#pragma unroll
+      for (int j = 0; j < TM; ++j) offA[ks][j] = ks_frag_off<BM>(lane, ks, (wm0 >> 5) + j);
+    } else {
+      offA[ks][0] = kc_frag_off(lane, ks) + wm0 * 64;
+    }
+    if constexpr (BKS) {
+#pragma unroll
+      for (int i = 0; i < TN; ++i) offB[ks][i] = ks_frag_off<BN>(lane, ks, (wn0 >> 5) + i) + A_BYTES;
+    } else {
+      offB[ks][0] = kc_frag_off(lane, ks) + wn0 * 64 + A_BYTES;
+    }
+  }
 
+  const int nk = (p.K + DMA_BK - 1) / DMA_BK;
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t) issue_tile(t);
+
+  const uint32_t smem_base = lds_addr(smem);
   const int fr = lane & 31, fh = lane >> 5;
   for (int kt = 0; kt < nk; ++kt) {
-    const uint8_t* sA = smem + (kt & 1) * STAGE;
-    const uint8_t* sB = sA + A_BYTES;
-    if (kt + 1 < nk) load_tiles((kt + 1) * TILE_K);
+    wait_vmcnt<(NST - 2) * LOADS_PER_TILE>();      // tile kt has landed; the younger tiles may be in flight
+    __builtin_amdgcn_s_barrier();                  // ... for every wave; and stage (kt-1)%NST is free again
+    issue_tile(kt + NST - 1);
+    const uint32_t st = smem_base + (kt % NST) * STAGE;
+    u32x4 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 fa[TM], fb[TN];
+    for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-      for (int j = 0; j < TM; ++j) fa[j] = lds_read_frag<AKS>(sA, wm0 + j * 32 + fr, 2 * ks + fh);
+      for (int j = 0; j < TM; ++j) {
+        if constexpr (AKS) {
+          const u32x2 lo = ds_read_tr_at<0>(st + offA[ks][j]), hi = ds_read_tr_at<8 * BM>(st + offA[ks][j]);
+          fa[ks][j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        } else {
+          fa[ks][j] = (j == 0) ? ds_read_b128_at<0>(st + offA[ks][0]) : (j == 1) ? ds_read_b128_at<2048>(st + offA[ks][0])
+                    : (j == 2) ? ds_read_b128_at<4096>(st + offA[ks][0]) : ds_read_b128_at<6144>(st + offA[ks][0]);
+        }
+      }
 #pragma unroll
-      for (int i = 0; i < TN; ++i) fb[i] = lds_read_frag<BKS>(sB, wn0 + i * 32 + fr, 2 * ks + fh);
+      for (int i = 0; i < TN; ++i) {
+        if constexpr (BKS) {
+          const u32x2 lo = ds_read_tr_at<0>(st + offB[ks][i]), hi = ds_read_tr_at<8 * BN>(st + offB[ks][i]);
+          fb[ks][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        } else {
+          fb[ks][i] = (i == 0) ? ds_read_b128_at<0>(st + offB[ks][0]) : (i == 1) ? ds_read_b128_at<2048>(st + offB[ks][0])
+                    : (i == 2) ? ds_read_b128_at<4096>(st + offB[ks][0]) : ds_read_b128_at<6144>(st + offB[ks][0]);
+        }
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      // LDS returns in order: after step 0's wait only step 1's reads may be outstanding.  The empty asm
+      // statements "use and define" the fragments so that no MFMA can be scheduled above the wait.
+      constexpr int STEP_READS = (AKS ? 2 * TM : TM) + (BKS ? 2 * TN : TN);
+      static_assert(STEP_READS <= 15, "lgkmcnt is a 4-bit counter");
+      if (ks == 0) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(STEP_READS) : "memory");
+      else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < TM; ++j) asm volatile("" : "+v"(fa[ks][j]));
+#pragma unroll
+      for (int i = 0; i < TN; ++i) asm volatile("" : "+v"(fb[ks][i]));
 #pragma unroll
       for (int i = 0; i < TN; ++i)
 #pragma unroll
         for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[ks][i]),
+                                                              __builtin_bit_cast(bf16x8, fa[ks][j]), acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) {
-      uint8_t* dA = smem + ((kt + 1) & 1) * STAGE;
-      mvA.store(dA, tid);
-      mvB.store(dA + A_BYTES, tid);
-    }
-    __syncthreads();
   }
+  wait_vmcnt<0>();     // the zero-fill loads issued past the last tile must land before the LDS is released
 
   // ---- epilogue: accumulator (i, j) value v is C[m][n] with
   //      m = m0 + wm0 + 32 j + lane%32,  n = n0 + wn0 + 32 i + 8 (v/4) + 4 (lane/32) + v%4
@@ -192,7 +238,7 @@ template <int BM, int BN, int WM, int WN, bool AKS, bool BKS, int EPI>
 hipError_t launch_cfg(const GemmArgs& a0, hipStream_t stream) {
   GemmArgs a = a0;
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
-  constexpr int LDS = 2 * (BM + BN) * TILE_ROW_BYTES;
+  constexpr int LDS = NST * (BM + BN) * DMA_BK * 2;
   const int n_logical = (EPI == EPI_SWIGLU) ? 2 * a.n_split : a.N;
   a.tiles_m = (a.M + BM - 1) / BM;
   a.a_bytes = AKS ? ((long)(a.K - 1) * a.lda + a.M) * 2 : ((long)(a.M - 1) * a.lda + a.K) * 2;
@@ -207,8 +253,7 @@ hipError_t launch_cfg(const GemmArgs& a0, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  const int per_xcd = (a.tiles_m * a.tiles_n + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(NT), LDS, stream, a);
+  hipLaunchKernelGGL(kern, dim3(a.tiles_m * a.tiles_n), dim3(NT), LDS, stream, a);
   return hipGetLastError();
 }
 

@@ -236,14 +236,27 @@ void norm_bwd_kernel(const NormBwdArgs p) {
   }
 }
 
-// out[col] (+)= sum_k part[k][col], k in fixed order: the second stage of every column reduction.
+// out[col] (+)= sum_k part[k][col]: the second stage of every column reduction.  A workgroup owns 32
+// columns; its 8 row groups each sum every 8th partial row, then the 8 group sums are added in
+// group order (a fixed summation tree: results do not depend on scheduling).
 __global__ __launch_bounds__(256)
 void colsum_finish_kernel(const float* __restrict__ part, int nparts, long stride, int n, float* __restrict__ out, int accumulate) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
-  if (col >= n) return;
+  __shared__ float red[8][32];
+  const int c = threadIdx.x & 31, kg = threadIdx.x >> 5;
+  const int col = blockIdx.x * 32 + c;
   float s = 0.0f;
-  for (int k = 0; k < nparts; ++k) s += part[(long)k * stride + col];
-  out[col] = accumulate ? out[col] + s : s;
+  if (col < n) {
+#pragma unroll 4
+    for (int k = kg; k < nparts; k += 8) s += part[(long)k * stride + col];
+  }
+  red[kg][c] = s;
+  __syncthreads();
+  if (kg == 0 && col < n) {
+    float t = red[0][c];
+#pragma unroll
+    for (int g = 1; g < 8; ++g) t += red[g][c];
+    out[col] = accumulate ? out[col] + t : t;
+  }
 }
 
 // part[blockIdx.y][col] = sum over this block's row range of g[row][col] (bf16 in, fp32 out).
@@ -321,7 +334,7 @@ hipError_t colsum_finish_launch(const float* part, int nparts, int n, float* out
 }
 
 hipError_t colsum_finish_strided_launch(const float* part, int nparts, long stride, int n, float* out, int accumulate, hipStream_t st) {
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, st, part, nparts, stride, n, out, accumulate);
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + 31) / 32), dim3(256), 0, st, part, nparts, stride, n, out, accumulate);
   return hipGetLastError();
 }
 
