@@ -269,12 +269,10 @@ hipError_t launch_layout(const GemmArgs& a, int tile_cfg, hipStream_t stream) {
 }  // namespace
 
 int gemm_pick_tile(int M, int N) {
-  // Big tiles need enough of them to cover the 256 CUs; otherwise fall back to smaller ones.
+  // One 128x128 workgroup already keeps a CU's MFMA pipes busy, and two fit per CU; the 256x256 tile
+  // halves the L2 -> LDS traffic per flop but only pays once there are several tiles per CU.
   const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-  if (t256 >= 48) return GEMM_TILE_256x256;
-  const long t128 = (long)((M + 255) / 256) * ((N + 127) / 128);
-  if (t128 >= 48) return GEMM_TILE_256x128;
-  return GEMM_TILE_128x128;
+  return t256 >= 512 ? GEMM_TILE_256x256 : GEMM_TILE_128x128;
 }
 
 hipError_t gemm_launch(int layout, int epi, const GemmArgs& a, int tile_cfg, hipStream_t stream) {

@@ -99,16 +99,25 @@ struct DmaLoader {
       base[i] = c >= 0 ? (uint32_t)(k * ld + c) * 2u : BUF_OOB;
     }
   }
-  DEV void issue(buf_rsrc rs, uint8_t* tile, int k0, int k_end, int wave) const {
+  // extra: a wave-uniform byte offset added to in-range lanes (e.g. a row offset of a KC operand)
+  DEV void issue(buf_rsrc rs, uint8_t* tile, int k0, int k_end, int wave, uint32_t extra = 0) const {
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
       uint32_t off;
-      if (KS) off = base[i] + (uint32_t)(k0 * ld2);
-      else off = (k0 + kofs < k_end) ? base[i] + (uint32_t)k0 * 2u : BUF_OOB;
+      if (KS) off = base[i] + (uint32_t)(k0 * ld2) + extra;
+      else off = (k0 + kofs < k_end) ? base[i] + (uint32_t)k0 * 2u + extra : BUF_OOB;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LDS_PTR(tile + (wave * IPW + i) * 1024), 16, off, 0, 0, 0);
     }
   }
 };
+
+// Explicit LDS waits for the asm reads: lds_wait<N>() returns once at most N LDS operations of this wave
+// are outstanding (they complete in order); tie() makes a register "used and redefined" after the wait
+// so that no consumer can be scheduled above it.
+template <int N>
+DEV void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
+DEV void tie(u32x4& v) { asm volatile("" : "+v"(v)); }
+DEV void tie(u32x2& v) { asm volatile("" : "+v"(v)); }
 
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14; expcnt, lgkmcnt left open)
 template <int N>
