@@ -7,8 +7,9 @@
 //   S^T[kv, q] = K Q^T          row statistics of a query are then a reduction over one lane's
 //   O^T[d, q]  = V^T P^T        registers plus one exchange between the two lane halves, and the
 // probabilities never leave registers: an accumulator converted to bf16 is directly the second
-// operand of the next product, provided the first operand's contraction index is gathered in the
-// accumulator's row order (MoverKS<.., PERM=true>).
+// operand of the next product, provided the first operand's contraction index is read in the
+// accumulator's row order (the transposing LDS reads below take their rows in that order).
+// Operand tiles travel HBM/L2 -> LDS with buffer_load ... lds, double buffered; see lds_dma.h.
 //
 // Backward is two passes without atomics (run-to-run identical results):
 //   dQ pass, one workgroup per 128 queries: recompute P^T from the saved log-sum-exp,
@@ -17,7 +18,8 @@
 //     dS = P (dP - D), dK^T += Q^T dS.
 // D[q] = sum_d dO[q,d] O[q,d] comes from a small pre-pass.
 #include "attention.h"
-#include "lds_tile.h"
+#include "lds_dma.h"
+#include <type_traits>
 
 namespace {
 
@@ -26,12 +28,8 @@ constexpr float LN2 = 0.6931471805599453f;
 
 template <int D>
 struct Dims {
-  static constexpr int DK = (D + 63) / 64;            // 64-wide contraction sub-tiles along d
-  static constexpr int DPAD = ((D + 31) / 32) * 32;   // rows of a transposed ([d][pos]) tile
-  static constexpr int DT = DPAD / 32;
+  static constexpr int DT = (D + 31) / 32;             // 32-row d tiles of a transposed (d x position) product
   static constexpr int KSTEPS = D / 16;               // MFMA steps of a contraction over d
-  static constexpr int KC_BYTES = DK * 64 * TILE_ROW_BYTES;   // [DK][64 pos][64 d]
-  static constexpr int KS_BYTES = DPAD * TILE_ROW_BYTES;      // [DPAD d][64 pos]
 };
 
 // B-operand fragments straight from HBM: lane (pos = row0 + lane%32, half) takes 8 consecutive d.
@@ -44,40 +42,6 @@ DEV void load_row_frags(const bf16_t* __restrict__ base, long ld, int pos, int s
     if (pos < seq) v = *reinterpret_cast<const u32x4*>(base + (long)pos * ld + ks * 16 + fh * 8);
     f[ks] = __builtin_bit_cast(bf16x8, v);
   }
-}
-
-// acc[t] (t = 0,1: two 32-row groups of the 64-position LDS tile) += Tile[32t.., d] * frag[d, lane]
-template <int D>
-DEV void mma_tile_rows(const uint8_t* kc_tile, const bf16x8 (&f)[Dims<D>::KSTEPS], int fr, int fh, f32x16 (&acc)[2]) {
-#pragma unroll
-  for (int ks = 0; ks < Dims<D>::KSTEPS; ++ks) {
-    const uint8_t* sub = kc_tile + (ks >> 2) * (64 * TILE_ROW_BYTES);
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const bf16x8 a = lds_read_frag<false>(sub, 32 * t + fr, 2 * (ks & 3) + fh);
-      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, f[ks], acc[t], 0, 0, 0);
-    }
-  }
-}
-
-// out[dt] += TileT[32dt.., pos] * bf16(vals)[pos, lane]; vals = two accumulators covering 64 positions
-template <int D>
-DEV void mma_tile_cols(const uint8_t* ks_tile, const f32x16 (&vals)[2], int fr, int fh, f32x16 (&out)[Dims<D>::DT]) {
-  bf16x8 pf[4];
-#pragma unroll
-  for (int s4 = 0; s4 < 4; ++s4) {
-    const int t = s4 >> 1, u = s4 & 1;
-    u32x4 w = {pack_bf16(vals[t][8 * u + 0], vals[t][8 * u + 1]), pack_bf16(vals[t][8 * u + 2], vals[t][8 * u + 3]),
-               pack_bf16(vals[t][8 * u + 4], vals[t][8 * u + 5]), pack_bf16(vals[t][8 * u + 6], vals[t][8 * u + 7])};
-    pf[s4] = __builtin_bit_cast(bf16x8, w);
-  }
-#pragma unroll
-  for (int dt = 0; dt < Dims<D>::DT; ++dt)
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) {
-      const bf16x8 a = lds_read_frag<true>(ks_tile, 32 * dt + fr, 2 * s4 + fh);
-      out[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[s4], out[dt], 0, 0, 0);
-    }
 }
 
 // accumulator register v of the lane half fh holds tile row 8 (v/4) + 4 fh + v%4
@@ -100,15 +64,33 @@ DEV void store_transposed(const f32x16 (&o)[Dims<D>::DT], float scale, bf16_t* _
 }
 
 // ------------------------------------------------------------------------------------- forward
+// compile-time loop: f(std::integral_constant<int, I>) for I in [0, N)
+template <int I, int N, class F>
+DEV void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// One workgroup = 128 queries of one (batch element, head): 4 waves x 32 queries.  K and V tiles of 64
+// keys travel HBM/L2 -> LDS with buffer_load ... lds (double buffered, no VGPR staging): K as
+// contraction-contiguous [kv][32 d] sub-tiles, V as row-major [32 kv][d] sub-tiles read back with the
+// transposing LDS read in accumulator-row order, so P feeds P V straight from registers.
 template <int D>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(256, 2)
 void attn_fwd_kernel(const AttnArgs p) {
   using X = Dims<D>;
-  constexpr int STAGE = X::KC_BYTES + X::KS_BYTES;      // K tile [kv][d] and V tile [d][kv]
-  extern __shared__ __align__(16) uint8_t smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int DS = (D + 31) / 32;                 // 32-wide d sub-tiles of K
+  constexpr int K_BYTES = DS * 4096;                // [DS][64 kv][32 d]
+  constexpr int V_BYTES = 2 * 8192;                 // [2][32 kv][128 d]
+  constexpr int STAGE = K_BYTES + V_BYTES;
+  constexpr int NB = (X::KSTEPS + 3) / 4;           // batches of up to 4 contraction steps over d
+  extern __shared__ __align__(1024) uint8_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x;            // longest rows first
+  const int qb = gridDim.x - 1 - blockIdx.x;        // longest rows first
   const int hh = blockIdx.y, bi = blockIdx.z;
   const int s = p.seq;
   const int qw0 = qb * 128 + wave * 32, qpos = qw0 + fr;
@@ -122,21 +104,29 @@ void attn_fwd_kernel(const AttnArgs p) {
   bf16x8 qf[X::KSTEPS];
   load_row_frags<D>(tok0 + hh * D, ld, qpos, s, fh, qf);
 
-  MoverKC<64, 256> mvK[X::DK];
-  MoverKS<X::DPAD, 256, true> mvV;
+  DmaLoader<64, 4, false> ldK;
+  DmaLoader<128, 4, true> ldV;
+  ldK.init_kc((int)ld, 0, 1 << 30, wave, lane);       // rows past the sequence end fall outside the extent
+  ldV.init_ks((int)ld, IdentityCols{0, D}, wave, lane);
+  auto issue_tile = [&](int j) {
+    uint8_t* st = smem + (j & 1) * STAGE;
+    const int kv0 = j * 64;
 #pragma unroll
-  for (int c = 0; c < X::DK; ++c) mvK[c].init((int)ld, 0, 1 << 30, tid);
-  mvV.init((int)ld, IdentityCols{0, D}, tid);
-  auto load_tiles = [&](int kv0) {
+    for (int c = 0; c < DS; ++c) ldK.issue(rsK, st + c * 4096, c * 32, D, wave, (uint32_t)kv0 * (uint32_t)ld * 2u);
 #pragma unroll
-    for (int c = 0; c < X::DK; ++c) mvK[c].load(rsK, c * 64, D, (uint32_t)kv0 * (uint32_t)ld * 2u);
-    mvV.load(rsV, kv0, 0);
+    for (int h2 = 0; h2 < 2; ++h2) ldV.issue(rsV, st + K_BYTES + h2 * 8192, kv0 + 32 * h2, 0, wave);
   };
-  auto store_tiles = [&](uint8_t* st) {
+
+  // per-lane LDS offsets: K fragment (row lane%32, chunk 2*step + lane/32) and V^T fragment rows d
+  const uint32_t offK0 = kc_frag_off(lane, 0), offK1 = kc_frag_off(lane, 1);
+  uint32_t offV[X::DT];
+  {
+    const int sl = lane & 15, nh = (lane >> 4) & 1;
+    const int kr = 4 * fh + (sl >> 2);
 #pragma unroll
-    for (int c = 0; c < X::DK; ++c) mvK[c].store(st + c * 64 * TILE_ROW_BYTES, tid);
-    mvV.store(st + X::KC_BYTES, tid);
-  };
+    for (int dt = 0; dt < X::DT; ++dt)
+      offV[dt] = (uint32_t)(kr * 256 + ((dt ^ (kr & 3)) << 6) + (16 * nh + 4 * (sl & 3)) * 2 + K_BYTES);
+  }
 
   const int q_end = min(qb * 128 + 128, s);
   const int ntiles = (q_end + 63) / 64;
@@ -147,54 +137,124 @@ void attn_fwd_kernel(const AttnArgs p) {
     for (int v = 0; v < 16; ++v) o[dt][v] = 0.0f;
   float m = -INFINITY, l = 0.0f;
   const float sc = p.scale * LOG2E;
+  const uint32_t smem_base = lds_addr(smem);
 
-  load_tiles(0);
-  store_tiles(smem);
-  __syncthreads();
+  issue_tile(0);
   for (int j = 0; j < ntiles; ++j) {
-    const uint8_t* st = smem + (j & 1) * STAGE;
+    wait_vmcnt<0>();                                  // tile j has landed (this wave's part)
+    __builtin_amdgcn_s_barrier();                     // ... everybody's part; the other stage is free
+    if (j + 1 < ntiles) issue_tile(j + 1);
     const int kv0 = j * 64;
-    if (j + 1 < ntiles) load_tiles(kv0 + 64);
-    if (kv0 <= qw0 + 31) {                               // this wave has unmasked keys in the tile
-      f32x16 sT[2];
+    if (kv0 > qw0 + 31) continue;                     // every key of the tile is masked for this wave
+    const uint32_t st = smem_base + (j & 1) * STAGE;
+
+    // ---- S^T[kv, q] = K Q^T: batches of 4 contraction steps, next batch's reads in flight
+    f32x16 sT[2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sT[t][v] = 0.0f;
-      mma_tile_rows<D>(st, qf, fr, fh, sT);
-      const bool diag = kv0 + 63 > qw0;
-      float mx = -INFINITY;
+      for (int v = 0; v < 16; ++v) sT[t][v] = 0.0f;
+    u32x4 kf[2][4][2];
+    auto read_batch = [&](auto bb) {
+      constexpr int B = decltype(bb)::value;
+      static_for<0, 4>([&](auto kk) {
+        constexpr int KS = B * 4 + decltype(kk)::value;
+        if constexpr (KS < X::KSTEPS) {
+          const uint32_t a = st + ((KS & 1) ? offK1 : offK0);
+          kf[B & 1][decltype(kk)::value][0] = ds_read_b128_at<(KS >> 1) * 4096>(a);
+          kf[B & 1][decltype(kk)::value][1] = ds_read_b128_at<(KS >> 1) * 4096 + 2048>(a);
+        }
+      });
+    };
+    read_batch(std::integral_constant<int, 0>{});
+    static_for<0, NB>([&](auto bb) {
+      constexpr int B = decltype(bb)::value;
+      constexpr int NEXT = (B + 1 < NB) ? ((X::KSTEPS - 4 * (B + 1)) < 4 ? (X::KSTEPS - 4 * (B + 1)) : 4) * 2 : 0;
+      if constexpr (B + 1 < NB) read_batch(std::integral_constant<int, B + 1>{});
+      lds_wait<NEXT>();
+      static_for<0, 4>([&](auto kk) {
+        constexpr int KS = B * 4 + decltype(kk)::value;
+        if constexpr (KS < X::KSTEPS) {
+          tie(kf[B & 1][decltype(kk)::value][0]);
+          tie(kf[B & 1][decltype(kk)::value][1]);
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+            sT[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[B & 1][decltype(kk)::value][t]),
+                                                            qf[KS], sT[t], 0, 0, 0);
+        }
+      });
+    });
+
+    // ---- online softmax; a lane owns one query (both lane halves: the two key halves of each 8)
+    float mx = -INFINITY;
+    if (kv0 + 63 > qw0) {                             // tile touches the diagonal: mask keys after the query
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          float x = sT[t][v] * sc;
-          if (diag && kv0 + 32 * t + acc_row(v, fh) > qpos) x = -INFINITY;
-          sT[t][v] = x;
-          mx = fmaxf(mx, x);
+          if (kv0 + 32 * t + acc_row(v, fh) > qpos) sT[t][v] = -INFINITY;
+          mx = fmaxf(mx, sT[t][v]);
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m, mx);                  // finite: key 0 is visible to every query
+    } else {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sT[t][v]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;       // scores scaled to the log2 domain (sc > 0)
+    const float m_new = fmaxf(m, mx);                  // finite: key 0 is visible to every query
+    if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {   // rescale only when some query's maximum moved
       const float alpha = exp2f(m - m_new);
-      float rs = 0.0f;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float e = exp2f(sT[t][v] - m_new);
-          sT[t][v] = e;
-          rs += e;
-        }
-      l = l * alpha + rs;
-      m = m_new;
+      l *= alpha;
 #pragma unroll
       for (int dt = 0; dt < X::DT; ++dt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
-      mma_tile_cols<D>(st + X::KC_BYTES, sT, fr, fh, o);
+      m = m_new;
     }
-    if (j + 1 < ntiles) store_tiles(smem + ((j + 1) & 1) * STAGE);
-    __syncthreads();
+    float rs = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float e = exp2f(sT[t][v] * sc - m);
+        sT[t][v] = e;
+        rs += e;
+      }
+    l += rs;
+    bf16x8 pf[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const int t = s4 >> 1, u = s4 & 1;
+      u32x4 w = {pack_bf16(sT[t][8 * u + 0], sT[t][8 * u + 1]), pack_bf16(sT[t][8 * u + 2], sT[t][8 * u + 3]),
+                 pack_bf16(sT[t][8 * u + 4], sT[t][8 * u + 5]), pack_bf16(sT[t][8 * u + 6], sT[t][8 * u + 7])};
+      pf[s4] = __builtin_bit_cast(bf16x8, w);
+    }
+
+    // ---- O^T[d, q] += V^T P^T, one 32-row d tile at a time, next tile's reads in flight
+    u32x2 vf[2][4][2];
+    auto read_v = [&](auto dd) {
+      constexpr int DTI = decltype(dd)::value;
+      static_for<0, 4>([&](auto ss) {
+        constexpr int S4 = decltype(ss)::value;
+        constexpr int OFF = (S4 >> 1) * 8192 + (S4 & 1) * 4096;
+        vf[DTI & 1][S4][0] = ds_read_tr_at<OFF>(st + offV[DTI]);
+        vf[DTI & 1][S4][1] = ds_read_tr_at<OFF + 2048>(st + offV[DTI]);
+      });
+    };
+    read_v(std::integral_constant<int, 0>{});
+    static_for<0, X::DT>([&](auto dd) {
+      constexpr int DTI = decltype(dd)::value;
+      if constexpr (DTI + 1 < X::DT) read_v(std::integral_constant<int, DTI + 1>{});
+      lds_wait<(DTI + 1 < X::DT) ? 8 : 0>();
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        tie(vf[DTI & 1][s4][0]);
+        tie(vf[DTI & 1][s4][1]);
+        const u32x4 a = {vf[DTI & 1][s4][0][0], vf[DTI & 1][s4][0][1], vf[DTI & 1][s4][1][0], vf[DTI & 1][s4][1][1]};
+        o[DTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pf[s4], o[DTI], 0, 0, 0);
+      }
+    });
   }
   l += __shfl_xor(l, 32, 64);
   if (qpos < s) {
@@ -224,14 +284,134 @@ void attn_dot_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dO
   dot[((long)bi * heads + hh) * seq + pos] = acc;
 }
 
+// ------------------------------------------------------------------------------------- backward tiles
+// Row-major LDS tile [64 positions][128 d] (16 KiB) filled by buffer_load ... lds, serving BOTH fragment
+// kinds of one operand: the plain fragment (row = position, 8 consecutive d: ds_read_b128) and the
+// transposed fragment (row = d, contraction over positions in accumulator-row order: two
+// ds_read_b64_tr_b16).  16-byte chunk c of row r lives at r*256 + ((c ^ rm_swz(r)) << 4): the 16 rows of a
+// plain read hit 16 distinct chunk positions, and the 4 rows x 2 column groups of a transposing
+// read hit 8 distinct 32-byte pairs.
+DEV int rm_swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+struct RmLoader {            // 4 waves x 4 one-KiB pieces (4 rows each)
+  uint32_t base[4];
+  DEV void init(int ld, int d_valid, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 4 * (wave * 4 + i) + (lane >> 4);
+      const int d = ((lane & 15) ^ rm_swz(row)) * 8;
+      base[i] = d < d_valid ? (uint32_t)(row * ld + d) * 2u : BUF_OOB;
+    }
+  }
+  DEV void issue(buf_rsrc rs, uint8_t* tile, uint32_t row_byte_off, int wave) const {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LDS_PTR(tile + (wave * 4 + i) * 1024), 16, base[i] + row_byte_off, 0, 0, 0);
+  }
+};
+// per-lane byte offset of the plain fragment (row lane%32, chunk lane/32) at contraction step 0; step ks
+// is reached by XOR (ks << 5), the second 32-row group by + 8192
+DEV uint32_t rm_plain_off(int lane) {
+  const int fr = lane & 31, fh = lane >> 5;
+  return (uint32_t)(fr * 256 + ((fh ^ rm_swz(fr)) << 4));
+}
+// per-lane byte offset of the first transposing read of the transposed fragment (d tile 0); d tile dt and
+// the second read are reached by XOR ((4 dt) ^ (2 second)) << 4; + 4096 u + 8192 sub + 2048 second
+DEV uint32_t rm_trans_off(int lane) {
+  const int sl = lane & 15, nh = (lane >> 4) & 1, fh = lane >> 5;
+  const int posl = 4 * fh + (sl >> 2);
+  const int h = (2 * nh + ((sl & 3) >> 1)) ^ rm_swz(posl);
+  return (uint32_t)(posl * 256 + (h << 4) + 8 * (sl & 1));
+}
+
+// acc[t] += Tile[32 t + lane%32, d] * frag[d, lane] over all d, batches of 4 steps with the next batch's
+// reads in flight.  tile_addr = LDS byte address of the row-major tile, off = rm_plain_off(lane).
+template <int D>
+DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>::KSTEPS], f32x16 (&acc)[2]) {
+  using X = Dims<D>;
+  constexpr int NB = (X::KSTEPS + 3) / 4;
+  u32x4 fr[2][4][2];
+  auto read_batch = [&](auto bb) {
+    constexpr int B = decltype(bb)::value;
+    static_for<0, 4>([&](auto kk) {
+      constexpr int KS = B * 4 + decltype(kk)::value;
+      if constexpr (KS < X::KSTEPS) {
+        const uint32_t a = tile_addr + (off ^ (KS << 5));
+        fr[B & 1][decltype(kk)::value][0] = ds_read_b128_at<0>(a);
+        fr[B & 1][decltype(kk)::value][1] = ds_read_b128_at<8192>(a);
+      }
+    });
+  };
+  read_batch(std::integral_constant<int, 0>{});
+  static_for<0, NB>([&](auto bb) {
+    constexpr int B = decltype(bb)::value;
+    constexpr int LEFT = X::KSTEPS - 4 * (B + 1);
+    constexpr int NEXT = (B + 1 < NB) ? (LEFT < 4 ? LEFT : 4) * 2 : 0;
+    if constexpr (B + 1 < NB) read_batch(std::integral_constant<int, B + 1>{});
+    lds_wait<NEXT>();
+    static_for<0, 4>([&](auto kk) {
+      constexpr int KS = B * 4 + decltype(kk)::value;
+      if constexpr (KS < X::KSTEPS) {
+        tie(fr[B & 1][decltype(kk)::value][0]);
+        tie(fr[B & 1][decltype(kk)::value][1]);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[B & 1][decltype(kk)::value][t]),
+                                                          f[KS], acc[t], 0, 0, 0);
+      }
+    });
+  });
+}
+
+// out[dt] += TileT[32 dt + lane%32, pos] * bf16(vals)[pos, lane]: vals = two accumulators covering the
+// tile's 64 positions; off = rm_trans_off(lane).
+template <int D>
+DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const f32x16 (&vals)[2], f32x16 (&out)[Dims<D>::DT]) {
+  using X = Dims<D>;
+  bf16x8 pf[4];
+#pragma unroll
+  for (int s4 = 0; s4 < 4; ++s4) {
+    const int t = s4 >> 1, u = s4 & 1;
+    u32x4 w = {pack_bf16(vals[t][8 * u + 0], vals[t][8 * u + 1]), pack_bf16(vals[t][8 * u + 2], vals[t][8 * u + 3]),
+               pack_bf16(vals[t][8 * u + 4], vals[t][8 * u + 5]), pack_bf16(vals[t][8 * u + 6], vals[t][8 * u + 7])};
+    pf[s4] = __builtin_bit_cast(bf16x8, w);
+  }
+  u32x2 vf[2][4][2];
+  auto read_v = [&](auto dd) {
+    constexpr int DTI = decltype(dd)::value;
+    static_for<0, 4>([&](auto ss) {
+      constexpr int S4 = decltype(ss)::value;
+      constexpr int OFF = (S4 >> 1) * 8192 + (S4 & 1) * 4096;
+      vf[DTI & 1][S4][0] = ds_read_tr_at<OFF>(tile_addr + (off ^ ((4 * DTI) << 4)));
+      vf[DTI & 1][S4][1] = ds_read_tr_at<OFF + 2048>(tile_addr + (off ^ (((4 * DTI) ^ 2) << 4)));
+    });
+  };
+  read_v(std::integral_constant<int, 0>{});
+  static_for<0, X::DT>([&](auto dd) {
+    constexpr int DTI = decltype(dd)::value;
+    if constexpr (DTI + 1 < X::DT) read_v(std::integral_constant<int, DTI + 1>{});
+    lds_wait<(DTI + 1 < X::DT) ? 8 : 0>();
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      tie(vf[DTI & 1][s4][0]);
+      tie(vf[DTI & 1][s4][1]);
+      const u32x4 a = {vf[DTI & 1][s4][0][0], vf[DTI & 1][s4][0][1], vf[DTI & 1][s4][1][0], vf[DTI & 1][s4][1][1]};
+      out[DTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI], 0, 0, 0);
+    }
+  });
+}
+
+constexpr int RM_TILE = 16384;
+
 // ------------------------------------------------------------------------------------- dQ pass
 template <int D>
 __global__ __launch_bounds__(256)
 void attn_bwd_dq_kernel(const AttnArgs p) {
   using X = Dims<D>;
-  constexpr int STAGE = 2 * X::KC_BYTES + X::KS_BYTES;  // K [kv][d], V [kv][d], K^T [d][kv]
-  extern __shared__ __align__(16) uint8_t smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int STAGE = 2 * RM_TILE;                      // K tile, V tile (64 keys each)
+  extern __shared__ __align__(1024) uint8_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
   const int qb = gridDim.x - 1 - blockIdx.x;
   const int hh = blockIdx.y, bi = blockIdx.z;
@@ -251,25 +431,15 @@ void attn_bwd_dq_kernel(const AttnArgs p) {
   const float lse2 = qpos < s ? p.lse[stat] * LOG2E : INFINITY;
   const float dq_dot = qpos < s ? p.dot[stat] : 0.0f;
 
-  MoverKC<64, 256> mvK[X::DK], mvV[X::DK];
-  MoverKS<X::DPAD, 256, true> mvKt;
-#pragma unroll
-  for (int c = 0; c < X::DK; ++c) { mvK[c].init((int)ld, 0, 1 << 30, tid); mvV[c].init((int)ld, 0, 1 << 30, tid); }
-  mvKt.init((int)ld, IdentityCols{0, D}, tid);
-  auto load_tiles = [&](int kv0) {
-    const uint32_t ro = (uint32_t)kv0 * (uint32_t)ld * 2u;
-#pragma unroll
-    for (int c = 0; c < X::DK; ++c) { mvK[c].load(rsK, c * 64, D, ro); mvV[c].load(rsV, c * 64, D, ro); }
-    mvKt.load(rsK, kv0, 0);
+  RmLoader ldr;
+  ldr.init((int)ld, D, wave, lane);
+  auto issue_tile = [&](int j) {
+    uint8_t* st = smem + (j & 1) * STAGE;
+    const uint32_t ro = (uint32_t)(j * 64) * (uint32_t)ld * 2u;
+    ldr.issue(rsK, st, ro, wave);
+    ldr.issue(rsV, st + RM_TILE, ro, wave);
   };
-  auto store_tiles = [&](uint8_t* st) {
-#pragma unroll
-    for (int c = 0; c < X::DK; ++c) {
-      mvK[c].store(st + c * 64 * TILE_ROW_BYTES, tid);
-      mvV[c].store(st + X::KC_BYTES + c * 64 * TILE_ROW_BYTES, tid);
-    }
-    mvKt.store(st + 2 * X::KC_BYTES, tid);
-  };
+  const uint32_t offP = rm_plain_off(lane), offT = rm_trans_off(lane);
 
   const int q_end = min(qb * 128 + 128, s);
   const int ntiles = (q_end + 63) / 64;
@@ -279,35 +449,33 @@ void attn_bwd_dq_kernel(const AttnArgs p) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) dq[dt][v] = 0.0f;
   const float sc = p.scale * LOG2E;
+  const uint32_t smem_base = lds_addr(smem);
 
-  load_tiles(0);
-  store_tiles(smem);
-  __syncthreads();
+  issue_tile(0);
   for (int j = 0; j < ntiles; ++j) {
-    const uint8_t* st = smem + (j & 1) * STAGE;
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (j + 1 < ntiles) issue_tile(j + 1);
     const int kv0 = j * 64;
-    if (j + 1 < ntiles) load_tiles(kv0 + 64);
-    if (kv0 <= qw0 + 31) {
-      f32x16 sT[2], dpT[2];
+    if (kv0 > qw0 + 31) continue;
+    const uint32_t st = smem_base + (j & 1) * STAGE;
+    f32x16 sT[2], dpT[2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sT[t][v] = 0.0f; dpT[t][v] = 0.0f; }
-      mma_tile_rows<D>(st, qf, fr, fh, sT);
-      mma_tile_rows<D>(st + X::KC_BYTES, dof, fr, fh, dpT);
-      const bool diag = kv0 + 63 > qw0;
+      for (int v = 0; v < 16; ++v) { sT[t][v] = 0.0f; dpT[t][v] = 0.0f; }
+    rm_mma_rows<D>(st, offP, qf, sT);                    // S^T  = K Q^T
+    rm_mma_rows<D>(st + RM_TILE, offP, dof, dpT);        // dP^T = V dO^T
+    const bool diag = kv0 + 63 > qw0;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float pr = exp2f(sT[t][v] * sc - lse2);
-          if (diag && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
-          sT[t][v] = pr * (dpT[t][v] - dq_dot);
-        }
-      mma_tile_cols<D>(st + 2 * X::KC_BYTES, sT, fr, fh, dq);
-    }
-    if (j + 1 < ntiles) store_tiles(smem + ((j + 1) & 1) * STAGE);
-    __syncthreads();
+      for (int v = 0; v < 16; ++v) {
+        float pr = exp2f(sT[t][v] * sc - lse2);
+        if (diag && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
+        sT[t][v] = pr * (dpT[t][v] - dq_dot);
+      }
+    rm_mma_cols<D>(st, offT, sT, dq);                    // dQ^T += K^T dS^T
   }
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + qpos) * ld + hh * D;
@@ -320,12 +488,12 @@ template <int D>
 __global__ __launch_bounds__(256)
 void attn_bwd_dkv_kernel(const AttnArgs p) {
   using X = Dims<D>;
-  constexpr int TILES = 2 * X::KC_BYTES + 2 * X::KS_BYTES;   // Q, dO [q][d]; Q^T, dO^T [d][q]
-  constexpr int STAGE = TILES + 2 * 64 * 4;                   // + lse2[64], dot[64]
-  extern __shared__ __align__(16) uint8_t smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int STAGE = 2 * RM_TILE + 512;                // Q tile, dO tile (64 queries), lse[64], dot[64]
+  extern __shared__ __align__(1024) uint8_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  const int kb = blockIdx.x;                                  // 128 keys per workgroup
+  const int kb = blockIdx.x;                              // 128 keys per workgroup
   const int hh = blockIdx.y, bi = blockIdx.z;
   const int s = p.seq;
   const int kw0 = kb * 128 + wave * 32, kpos = kw0 + fr;
@@ -335,97 +503,81 @@ void attn_bwd_dkv_kernel(const AttnArgs p) {
   const int hl = p.heads * D;
   const buf_rsrc rsQ = make_rsrc(tok0 + hh * D, ((long)(s - 1) * ld + D) * 2);
   const buf_rsrc rsO = make_rsrc(do0, ((long)(s - 1) * ldc + D) * 2);
-  const float* lse = p.lse + ((long)bi * p.heads + hh) * s;
-  const float* dot = p.dot + ((long)bi * p.heads + hh) * s;
+  const long stat0 = ((long)bi * p.heads + hh) * s;
+  const buf_rsrc rsL = make_rsrc(p.lse + stat0, (long)s * 4);   // rows past the end read as 0: harmless, their
+  const buf_rsrc rsD = make_rsrc(p.dot + stat0, (long)s * 4);   // Q and dO rows are zero as well
 
   bf16x8 kf[X::KSTEPS], vf[X::KSTEPS];
   load_row_frags<D>(tok0 + hl + hh * D, ld, kpos, s, fh, kf);
   load_row_frags<D>(tok0 + 2 * hl + hh * D, ld, kpos, s, fh, vf);
 
-  MoverKC<64, 256> mvQ[X::DK], mvO[X::DK];
-  MoverKS<X::DPAD, 256, true> mvQt, mvOt;
-#pragma unroll
-  for (int c = 0; c < X::DK; ++c) { mvQ[c].init((int)ld, 0, 1 << 30, tid); mvO[c].init((int)ldc, 0, 1 << 30, tid); }
-  mvQt.init((int)ld, IdentityCols{0, D}, tid);
-  mvOt.init((int)ldc, IdentityCols{0, D}, tid);
-  float st_lse = 0.0f, st_dot = 0.0f;
-  auto load_tiles = [&](int q0) {
-#pragma unroll
-    for (int c = 0; c < X::DK; ++c) {
-      mvQ[c].load(rsQ, c * 64, D, (uint32_t)q0 * (uint32_t)ld * 2u);
-      mvO[c].load(rsO, c * 64, D, (uint32_t)q0 * (uint32_t)ldc * 2u);
-    }
-    mvQt.load(rsQ, q0, 0);
-    mvOt.load(rsO, q0, 0);
-    if (tid < 64) {
-      const int q = q0 + tid;
-      st_lse = q < s ? lse[q] * LOG2E : INFINITY;     // exp2(x - inf) = 0 for rows past the end
-      st_dot = q < s ? dot[q] : 0.0f;
-    }
+  RmLoader ldq, ldo;
+  ldq.init((int)ld, D, wave, lane);
+  ldo.init((int)ldc, D, wave, lane);
+  auto issue_tile = [&](int j, int slot) {
+    uint8_t* st = smem + slot * STAGE;
+    ldq.issue(rsQ, st, (uint32_t)(j * 64) * (uint32_t)ld * 2u, wave);
+    ldo.issue(rsO, st + RM_TILE, (uint32_t)(j * 64) * (uint32_t)ldc * 2u, wave);
+    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsL, LDS_PTR(st + 2 * RM_TILE), 4, (uint32_t)(j * 64 + lane) * 4u, 0, 0, 0);
+    if (wave == 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsD, LDS_PTR(st + 2 * RM_TILE + 256), 4, (uint32_t)(j * 64 + lane) * 4u, 0, 0, 0);
   };
-  auto store_tiles = [&](uint8_t* st) {
-#pragma unroll
-    for (int c = 0; c < X::DK; ++c) {
-      mvQ[c].store(st + c * 64 * TILE_ROW_BYTES, tid);
-      mvO[c].store(st + X::KC_BYTES + c * 64 * TILE_ROW_BYTES, tid);
-    }
-    mvQt.store(st + 2 * X::KC_BYTES, tid);
-    mvOt.store(st + 2 * X::KC_BYTES + X::KS_BYTES, tid);
-    if (tid < 64) {
-      float* f = reinterpret_cast<float*>(st + TILES);
-      f[tid] = st_lse;
-      f[64 + tid] = st_dot;
-    }
-  };
+  const uint32_t offP = rm_plain_off(lane), offT = rm_trans_off(lane);
 
   const int nq = (s + 63) / 64;
-  const int j0 = (kb * 128) / 64;                       // first query tile that sees these keys
+  const int j0 = (kb * 128) / 64;                         // first query tile that sees these keys
   f32x16 dk[X::DT], dv[X::DT];
 #pragma unroll
   for (int dt = 0; dt < X::DT; ++dt)
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.0f; dv[dt][v] = 0.0f; }
   const float sc = p.scale * LOG2E;
+  const uint32_t smem_base = lds_addr(smem);
 
-  load_tiles(j0 * 64);
-  store_tiles(smem);
-  __syncthreads();
+  issue_tile(j0, 0);
   for (int j = j0; j < nq; ++j) {
-    const uint8_t* st = smem + ((j - j0) & 1) * STAGE;
+    const int slot = (j - j0) & 1;
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (j + 1 < nq) issue_tile(j + 1, slot ^ 1);
     const int q0 = j * 64;
-    if (j + 1 < nq) load_tiles(q0 + 64);
-    if (q0 + 63 >= kw0) {                                // some query of the tile sees this wave's keys
-      f32x16 sm[2], dpm[2];
+    if (q0 + 63 < kw0) continue;                          // no query of the tile sees this wave's keys
+    const uint32_t st = smem_base + slot * STAGE;
+    f32x16 sm[2], dpm[2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sm[t][v] = 0.0f; dpm[t][v] = 0.0f; }
-      mma_tile_rows<D>(st, kf, fr, fh, sm);                        // S[q, kv]
-      mma_tile_rows<D>(st + X::KC_BYTES, vf, fr, fh, dpm);         // dP[q, kv]
-      const float* f_lse = reinterpret_cast<const float*>(st + TILES);
-      const bool diag = q0 < kw0 + 31;
-      f32x16 pm[2];
+      for (int v = 0; v < 16; ++v) { sm[t][v] = 0.0f; dpm[t][v] = 0.0f; }
+    rm_mma_rows<D>(st, offP, kf, sm);                     // S[q, kv]  = Q K^T
+    rm_mma_rows<D>(st + RM_TILE, offP, vf, dpm);          // dP[q, kv] = dO V^T
+    const bool diag = q0 < kw0 + 31;
+    f32x16 pm[2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t) {
+      u32x4 l4[4], d4[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int r0 = 32 * t + 8 * g + 4 * fh;                  // 4 consecutive query rows
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(f_lse + r0);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(f_lse + 64 + r0);
+      for (int g = 0; g < 4; ++g) {                       // 4 consecutive query rows 32 t + 8 g + 4 fh ..
+        const uint32_t a = st + 2 * RM_TILE + (uint32_t)(32 * t + 8 * g + 4 * fh) * 4u;
+        l4[g] = ds_read_b128_at<0>(a);
+        d4[g] = ds_read_b128_at<256>(a);
+      }
+      lds_wait<0>();
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int v = 4 * g + e;
-            float pr = exp2f(sm[t][v] * sc - l4[e]);
-            if (diag && q0 + r0 + e < kpos) pr = 0.0f;
-            pm[t][v] = pr;
-            sm[t][v] = pr * (dpm[t][v] - d4[e]);
-          }
+      for (int g = 0; g < 4; ++g) {
+        tie(l4[g]);
+        tie(d4[g]);
+        const f32x4 lf = __builtin_bit_cast(f32x4, l4[g]), df = __builtin_bit_cast(f32x4, d4[g]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v = 4 * g + e;
+          float pr = exp2f(sm[t][v] * sc - lf[e] * LOG2E);
+          if (diag && q0 + 32 * t + 8 * g + 4 * fh + e < kpos) pr = 0.0f;
+          pm[t][v] = pr;
+          sm[t][v] = pr * (dpm[t][v] - df[e]);
         }
-      mma_tile_cols<D>(st + 2 * X::KC_BYTES + X::KS_BYTES, pm, fr, fh, dv);   // dV^T += dO^T P
-      mma_tile_cols<D>(st + 2 * X::KC_BYTES, sm, fr, fh, dk);                 // dK^T += Q^T dS
+      }
     }
-    if (j + 1 < nq) store_tiles(smem + ((j + 1 - j0) & 1) * STAGE);
-    __syncthreads();
+    rm_mma_cols<D>(st + RM_TILE, offT, pm, dv);           // dV^T += dO^T P
+    rm_mma_cols<D>(st, offT, sm, dk);                     // dK^T += Q^T dS
   }
   if (kpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + kpos) * ld + hh * D;
@@ -444,8 +596,7 @@ hipError_t set_lds(K kern, int bytes, bool& done) {
 
 template <int D>
 hipError_t fwd_launch(const AttnArgs& a, hipStream_t st) {
-  using X = Dims<D>;
-  constexpr int LDS = 2 * (X::KC_BYTES + X::KS_BYTES);
+  constexpr int LDS = 2 * (((D + 31) / 32) * 4096 + 2 * 8192);
   static bool done = false;
   hipError_t e = set_lds(attn_fwd_kernel<D>, LDS, done);
   if (e != hipSuccess) return e;
@@ -455,15 +606,14 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t st) {
 
 template <int D>
 hipError_t bwd_launch(const AttnArgs& a, hipStream_t st) {
-  using X = Dims<D>;
   const long rows = (long)a.batch * a.seq;
   hipLaunchKernelGGL(attn_dot_kernel, dim3((unsigned)((rows * a.heads + 255) / 256)), dim3(256), 0, st,
                      static_cast<const bf16_t*>(a.ctx), static_cast<const bf16_t*>(a.dctx), a.ld_ctx, (int)rows, a.seq,
                      a.heads, D, a.dot);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  constexpr int LDS_Q = 2 * (2 * X::KC_BYTES + X::KS_BYTES);
-  constexpr int LDS_KV = 2 * (2 * X::KC_BYTES + 2 * X::KS_BYTES + 512);
+  constexpr int LDS_Q = 2 * 2 * RM_TILE;
+  constexpr int LDS_KV = 2 * (2 * RM_TILE + 512);
   static bool done_q = false, done_kv = false;
   if ((e = set_lds(attn_bwd_dq_kernel<D>, LDS_Q, done_q)) != hipSuccess) return e;
   if ((e = set_lds(attn_bwd_dkv_kernel<D>, LDS_KV, done_kv)) != hipSuccess) return e;
