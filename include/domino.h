@@ -128,7 +128,7 @@ enum { DOMINO_EPI_STORE = 0,      /* C = bf16(acc + bias)                       
        DOMINO_EPI_ACC_F32 = 5 };  /* C(fp32) = acc, or += acc if beta                        TN     */
 
 /* bf16 MFMA product with fp32 accumulation.  M, N, K and all leading dimensions (in elements) must be
- * multiples of 8.  tile: -1 = choose by shape, 0 = 128x128, 1 = 256x128, 2 = 256x256 workgroup tile.
+ * multiples of 8.  tile: -1 = choose by shape, 0 = 128x128, 1 = 256x128, 2 = 256x256, 3 = 128x256 workgroup tile.
  * bias: bf16 [N] or NULL.  Invalid layout/epilogue pairs return DOMINO_ERR_INVALID_ARG. */
 int domino_gemm(int layout, int epilogue, int tile,
                 const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,

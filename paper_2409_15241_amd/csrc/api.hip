@@ -49,11 +49,14 @@ struct Layout {
   // saved block (bytes)
   size_t ln1, qkv, ctx, lse, x1, ln2, pre, act, mean1, rstd1, mean2, rstd2, saved_total;
   // workspace block (bytes)
-  size_t d_pre, dx1, dctx, dqkv, dot, red, slots, ws_total;
-  size_t red_floats, slot_floats;   // per-slice reduction scratch; one slot vector
+  size_t d_pre, dx1, dctx, dqkv, dot, red, ws_total;
+  // per-slice block of partial column sums: area k starts area_off[k] floats in and holds area_rows[k]
+  // rows of area_n[k] floats; red_floats = size of one slice's block
+  size_t red_floats, area_off[8];
+  int area_rows[8], area_n[8];
 };
 
-enum { SLOT_G1 = 0, SLOT_B1, SLOT_G2, SLOT_B2, SLOT_BQKV, SLOT_BO, SLOT_BUP, SLOT_BDOWN, NSLOTS };
+enum { AREA_G1 = 0, AREA_B1, AREA_G2, AREA_B2, AREA_BQKV, AREA_BO, AREA_BUP, AREA_BDOWN, NAREAS };
 
 int validate(const domino_cfg* c, Layout* L) {
   if (!c) return fail(DOMINO_ERR_NULL_POINTER, "cfg is NULL");
@@ -110,12 +113,18 @@ int validate(const domino_cfg* c, Layout* L) {
   l.dctx = take(Mz * l.hl * 2);
   l.dqkv = take(Mz * 3 * l.hl * 2);
   l.dot = take((size_t)l.b * l.nl * l.s * 4);
-  const size_t norm_fl = 2 * (size_t)norm_bwd_blocks(l.Ms) * l.h;
-  const size_t col_fl = (size_t)COLSUM_PARTS * widest;
-  l.red_floats = norm_fl > col_fl ? norm_fl : col_fl;
-  l.slot_floats = (size_t)widest;
+  {
+    const int nb = norm_bwd_blocks(l.Ms);
+    const int rows[NAREAS] = {nb, nb, nb, nb, COLSUM_PARTS, COLSUM_PARTS, COLSUM_PARTS, COLSUM_PARTS};
+    const int width[NAREAS] = {l.h, l.h, l.h, l.h, 3 * l.hl, l.h, l.fl, l.h};
+    size_t fo = 0;
+    for (int k = 0; k < NAREAS; ++k) {
+      l.area_off[k] = fo; l.area_rows[k] = rows[k]; l.area_n[k] = width[k];
+      fo += (size_t)rows[k] * width[k];
+    }
+    l.red_floats = (fo + 63) / 64 * 64;
+  }
   l.red = take((size_t)l.p * l.red_floats * 4);
-  l.slots = take((size_t)l.p * NSLOTS * l.slot_floats * 4);
   l.ws_total = o;
   if (L) *L = l;
   return DOMINO_OK;
@@ -428,8 +437,7 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
     char* dqkv = at(ws, L.dqkv + r0 * 3 * L.hl * 2);
     float* dot = reinterpret_cast<float*>(at(ws, L.dot)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
     float* red = reinterpret_cast<float*>(at(ws, L.red)) + (size_t)i * L.red_floats;
-    float* slots = reinterpret_cast<float*>(at(ws, L.slots)) + (size_t)i * NSLOTS * L.slot_floats;
-    auto slot = [&](int k) { return slots + (size_t)k * L.slot_floats; };
+    auto area = [&](int k) { return red + L.area_off[k]; };
     const int beta = (i > 0 || accumulate) ? 1 : 0;
     const bool chain = prev && prev != st;      // weight gradients are summed over slices in slice order
 
@@ -448,8 +456,7 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
     };
     auto colsum = [&](const void* g, long ld, int n, int k) -> int {
       ProfScope ps(PC_COLSUM, st);
-      LAUNCH(colsum_partial_launch(g, ld, Ms, n, red, st), "bias gradient");
-      LAUNCH(colsum_finish_launch(red, COLSUM_PARTS, n, slot(k), 0, st), "bias gradient");
+      LAUNCH(colsum_partial_launch(g, ld, Ms, n, area(k), st), "bias gradient");
       return DOMINO_OK;
     };
     auto norm_bwd = [&](const void* ga, const void* gb, const void* xin, const void* gamma, const float* mean,
@@ -457,10 +464,8 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
       ProfScope ps(PC_NORM_BWD, st);
       NormBwdArgs a{};
       a.ga = ga; a.gb = gb; a.x = xin; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dres = dres; a.dx = out;
-      a.part_g = red; a.part_b = red + (size_t)norm_bwd_blocks(Ms) * L.h; a.rows = Ms; a.h = L.h; a.rms = rms;
+      a.part_g = area(kg); a.part_b = area(kb); a.rows = Ms; a.h = L.h; a.rms = rms;
       LAUNCH(norm_bwd_launch(a, st), "norm backward");
-      LAUNCH(colsum_finish_launch(a.part_g, norm_bwd_blocks(Ms), L.h, slot(kg), 0, st), "norm gain gradient");
-      if (!rms) LAUNCH(colsum_finish_launch(a.part_b, norm_bwd_blocks(Ms), L.h, slot(kb), 0, st), "norm shift gradient");
       return DOMINO_OK;
     };
 
@@ -472,24 +477,24 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
       else LAUNCH(gemm_launch(GEMM_NT, EPI_DGELU, a, -1, st), "mlp-down input gradient");
     }
     TRY(wgrad(0, PC_WGRAD_DOWN, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
-    if (!L.llama) TRY(colsum(dyi, L.h, L.h, SLOT_BDOWN));
+    if (!L.llama) TRY(colsum(dyi, L.h, L.h, AREA_BDOWN));
     {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
       ProfScope ps(PC_DGRAD_UP, st);
       GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(dln2_partial, rh), L.h, Ms, L.h, L.upc);
       LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "mlp-up input gradient");
     }
     TRY(wgrad(1, PC_WGRAD_UP, ln2, L.h, d_pre, L.upc, G->w_up, L.upc, L.h, L.upc));
-    if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, SLOT_BUP));
+    if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, AREA_BUP));
     // B5
     TRY(norm_bwd(at(dln2_partial, rh), dln2_others ? at(dln2_others, rh) : nullptr, x1, P->norm2_g, mean2, rstd2,
-                 dyi, dx1, SLOT_G2, SLOT_B2));
+                 dyi, dx1, AREA_G2, AREA_B2));
     {  // B6
       ProfScope ps(PC_DGRAD_OUT, st);
       GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
       LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "out-projection input gradient");
     }
     TRY(wgrad(2, PC_WGRAD_OUT, ctx, L.hl, dx1, L.h, G->w_o, L.h, L.hl, L.h));
-    if (!L.llama) TRY(colsum(dx1, L.h, L.h, SLOT_BO));
+    if (!L.llama) TRY(colsum(dx1, L.h, L.h, AREA_BO));
     {  // B7
       ProfScope ps(PC_ATTN_BWD, st);
       AttnArgs a{};
@@ -508,29 +513,31 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
       LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "qkv input gradient");
     }
     TRY(wgrad(3, PC_WGRAD_QKV, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
-    if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, SLOT_BQKV));
+    if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, AREA_BQKV));
     TRY(norm_bwd(at(dln1_partial, rh), dln1_others ? at(dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
-                 dx1, at(dx, rh), SLOT_G1, SLOT_B1));
+                 dx1, at(dx, rh), AREA_G1, AREA_B1));
 
     prev = st;
     for (int k = 0; k < 4; ++k) wg_prev[k] = wg_cur[k];
   }
   for (int k = 1; k < nused; ++k) TRY(edge(as_stream(streams[k]), s0));
 
-  // vector gradients: sum the per-slice slots in slice order
+  // vector gradients: one launch sums, for every vector, the partial rows of all slices in slice order
   {
     ProfScope ps(PC_COLSUM, s0);
-    float* slots = reinterpret_cast<float*>(at(ws, L.slots));
-    const size_t stride = L.slot_floats;     // consecutive slots of one slice; slices NSLOTS*stride apart
-    struct { int k; float* out; int n; } vec[NSLOTS] = {
-      {SLOT_G1, G->norm1_g, L.h}, {SLOT_B1, G->norm1_b, L.h}, {SLOT_G2, G->norm2_g, L.h}, {SLOT_B2, G->norm2_b, L.h},
-      {SLOT_BQKV, G->b_qkv, 3 * L.hl}, {SLOT_BO, G->b_o, L.h}, {SLOT_BUP, G->b_up, L.fl}, {SLOT_BDOWN, G->b_down, L.h}};
+    float* red0 = reinterpret_cast<float*>(at(ws, L.red));
+    struct { int k; float* out; } vec[NAREAS] = {
+      {AREA_G1, G->norm1_g}, {AREA_B1, G->norm1_b}, {AREA_G2, G->norm2_g}, {AREA_B2, G->norm2_b},
+      {AREA_BQKV, G->b_qkv}, {AREA_BO, G->b_o}, {AREA_BUP, G->b_up}, {AREA_BDOWN, G->b_down}};
+    ColsumJobs jobs{};
+    int njobs = 0;
     for (auto& v : vec) {
       if (!v.out) continue;
-      if (L.llama && v.k != SLOT_G1 && v.k != SLOT_G2) continue;
-      LAUNCH(colsum_finish_strided_launch(slots + (size_t)v.k * stride, L.p, NSLOTS * stride, v.n, v.out, accumulate, s0),
-             "vector gradient reduction");
+      if (L.llama && v.k != AREA_G1 && v.k != AREA_G2) continue;
+      jobs.job[njobs++] = {red0 + L.area_off[v.k], v.out, L.area_rows[v.k], L.area_n[v.k], (long)L.area_n[v.k],
+                           L.p, (long)L.red_floats};
     }
+    LAUNCH(colsum_finish_jobs_launch(jobs, njobs, accumulate, s0), "vector gradient reduction");
   }
   return DOMINO_OK;
 }
@@ -543,7 +550,7 @@ int domino_gemm(int layout, int epilogue, int tile,
   if (!A || !B || !C) return fail(DOMINO_ERR_NULL_POINTER, "A, B or C is NULL");
   if (M <= 0 || N <= 0 || K <= 0) return fail(DOMINO_ERR_INVALID_ARG, "M, N, K must be positive");
   if (M % 8 || N % 8 || K % 8 || lda % 8 || ldb % 8 || ldc % 4) return fail(DOMINO_ERR_UNSUPPORTED, "dimensions must be multiples of 8");
-  if (tile < -1 || tile > 2) return fail(DOMINO_ERR_INVALID_ARG, "tile %d outside [-1, 2]", tile);
+  if (tile < -1 || tile > 3) return fail(DOMINO_ERR_INVALID_ARG, "tile %d outside [-1, 3]", tile);
   const bool ok = (layout == DOMINO_GEMM_NN && (epilogue == DOMINO_EPI_STORE || epilogue == DOMINO_EPI_BIAS_GELU || epilogue == DOMINO_EPI_SWIGLU)) ||
                   (layout == DOMINO_GEMM_NT && (epilogue == DOMINO_EPI_STORE || epilogue == DOMINO_EPI_DGELU || epilogue == DOMINO_EPI_DSWIGLU)) ||
                   (layout == DOMINO_GEMM_TN && epilogue == DOMINO_EPI_ACC_F32);
@@ -596,8 +603,10 @@ int domino_norm_bwd(const void* ga, const void* gb, const void* x, const void* g
   a.part_g = scratch; a.part_b = scratch + (size_t)nb * h; a.rows = rows; a.h = h; a.rms = rms;
   hipStream_t st = as_stream(stream);
   HIP_TRY(norm_bwd_launch(a, st), "norm backward launch");
-  HIP_TRY(colsum_finish_launch(a.part_g, nb, h, dgamma, 0, st), "norm gain gradient");
-  if (!rms) HIP_TRY(colsum_finish_launch(a.part_b, nb, h, dbeta, 0, st), "norm shift gradient");
+  ColsumJobs jobs{};
+  jobs.job[0] = {a.part_g, dgamma, nb, h, (long)h, 1, 0};
+  jobs.job[1] = {a.part_b, dbeta, nb, h, (long)h, 1, 0};
+  HIP_TRY(colsum_finish_jobs_launch(jobs, rms ? 1 : 2, 0, st), "norm gain / shift gradient");
   return DOMINO_OK;
 }
 

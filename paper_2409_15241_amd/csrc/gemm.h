@@ -12,7 +12,7 @@ enum GemmEpilogue {
   EPI_DSWIGLU = 4,    // C[:, n] = acc * up * silu'(gate); C[:, n_split + n] = acc * silu(gate)
   EPI_ACC_F32 = 5,    // C(fp32) = acc (+ C if beta)
 };
-enum GemmTile { GEMM_TILE_128x128 = 0, GEMM_TILE_256x128 = 1, GEMM_TILE_256x256 = 2 };
+enum GemmTile { GEMM_TILE_128x128 = 0, GEMM_TILE_256x128 = 1, GEMM_TILE_256x256 = 2, GEMM_TILE_128x256 = 3 };
 
 struct GemmArgs {
   const void* A; const void* B; void* C;

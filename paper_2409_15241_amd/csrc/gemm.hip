@@ -17,6 +17,7 @@
 // The MFMA is issued with the roles swapped (first operand = B fragment) so that a lane ends up
 // with 4 consecutive n for one m: 8-byte bf16 / 16-byte fp32 stores.
 #include "gemm.h"
+#include <cstdlib>
 #include "lds_dma.h"
 
 namespace {
@@ -262,6 +263,7 @@ hipError_t launch_layout(const GemmArgs& a, int tile_cfg, hipStream_t stream) {
   switch (tile_cfg) {
     case GEMM_TILE_256x256: return launch_cfg<256, 256, 128, 64, AKS, BKS, EPI>(a, stream);
     case GEMM_TILE_256x128: return launch_cfg<256, 128, 128, 64, AKS, BKS, EPI>(a, stream);
+    case GEMM_TILE_128x256: return launch_cfg<128, 256, 64, 128, AKS, BKS, EPI>(a, stream);
     default:                return launch_cfg<128, 128, 64, 64, AKS, BKS, EPI>(a, stream);
   }
 }
@@ -271,7 +273,11 @@ hipError_t launch_layout(const GemmArgs& a, int tile_cfg, hipStream_t stream) {
 int gemm_pick_tile(int M, int N) {
   // One 128x128 workgroup already keeps a CU's MFMA pipes busy, and two fit per CU; the 256x256 tile
   // halves the L2 -> LDS traffic per flop but only pays once there are several tiles per CU.
+  static const int policy = getenv("DOMINO_TILE_POLICY") ? atoi(getenv("DOMINO_TILE_POLICY")) : 0;
   const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (policy == 1 && M % 256 == 0 && N % 256 == 0) return GEMM_TILE_256x256;
+  if (policy == 2 && N % 256 == 0) return GEMM_TILE_128x256;
+  if (policy == 3 && M % 256 == 0) return GEMM_TILE_256x128;
   return t256 >= 512 ? GEMM_TILE_256x256 : GEMM_TILE_128x128;
 }
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 constexpr int NORM_BWD_MAX_BLOCKS = 256;   // one partial row of d gamma / d beta per workgroup
+constexpr int NORM_BWD_ROWS = 16;          // rows per workgroup until the block limit is reached
 constexpr int COLSUM_PARTS = 64;           // row ranges of the first column-sum stage
 
 struct NormFwdArgs {
@@ -39,7 +40,11 @@ hipError_t norm_fwd_launch(const NormFwdArgs& a, hipStream_t st);
 hipError_t norm_bwd_launch(const NormBwdArgs& a, hipStream_t st);
 // out[n] (+)= sum over nparts rows of part[nparts][n], summed in index order
 hipError_t colsum_finish_launch(const float* part, int nparts, int n, float* out, int accumulate, hipStream_t st);
-// same with the partial rows `stride` floats apart
-hipError_t colsum_finish_strided_launch(const float* part, int nparts, long stride, int n, float* out, int accumulate, hipStream_t st);
+// several such reductions in one launch; a job sums nouter groups (ostride floats apart) of nparts
+// partial rows (stride floats apart), group by group
+constexpr int COLSUM_MAX_JOBS = 8;
+struct ColsumJob { const float* part; float* out; int nparts, n; long stride; int nouter; long ostride; };
+struct ColsumJobs { ColsumJob job[COLSUM_MAX_JOBS]; };
+hipError_t colsum_finish_jobs_launch(const ColsumJobs& jobs, int njobs, int accumulate, hipStream_t st);
 // part[COLSUM_PARTS][n] = partial column sums of the bf16 matrix g[rows][ld]
 hipError_t colsum_partial_launch(const void* g, long ld, int rows, int n, float* part, hipStream_t st);

@@ -121,141 +121,133 @@ void norm_fwd_kernel(const NormFwdArgs p) {
 }
 
 // dx = dres + NormBwd(ga + gb); per-workgroup partial sums of d gamma / d beta.
-// A wave walks rows wave_id, wave_id + total_waves, ... and keeps the column sums of its lanes'
-// columns in registers; the 4 waves of a workgroup then combine through LDS in a fixed order.
-template <int NC, bool RMS>
-__global__ __launch_bounds__(256)
-void norm_bwd_kernel(const NormBwdArgs p) {
-  extern __shared__ float red[];      // [2][h]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// A workgroup owns a contiguous range of rows and walks it R rows at a time; thread t owns the 8
+// columns of 16-byte chunk t in every row, so its share of the column sums (d gamma, d beta) is 16
+// registers and every load of an iteration (R rows x up to 4 tensors) is in flight at once.  The two
+// row sums cross the waves through LDS: wave sums in a double-buffered table, one barrier per
+// iteration, added in wave order (fixed summation order).
+template <int NT, int R, bool RMS>
+__global__ __launch_bounds__(NT)
+void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
+  constexpr int NW = NT / 64;
+  __shared__ __align__(16) float red[2][NW][2 * R];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nw = blockDim.x >> 6;
   const int nch = p.h >> 3;
+  const bool live = tid < nch;
   const float inv_h = 1.0f / (float)p.h;
-  const u32x4* gam = reinterpret_cast<const u32x4*>(p.gamma);
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-  float dg[NC][8], db[RMS ? 1 : NC][8];
+  float gm[8];
+  unpack8(live ? reinterpret_cast<const u32x4*>(p.gamma)[tid] : zero4, gm);
+  float dg[8], db[8];
 #pragma unroll
-  for (int i = 0; i < NC; ++i)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { dg[i][e] = 0.0f; if (!RMS) db[i][e] = 0.0f; }
+  for (int e = 0; e < 8; ++e) { dg[e] = 0.0f; db[e] = 0.0f; }
 
-  for (int row = blockIdx.x * 4 + wave; row < p.rows; row += gridDim.x * 4) {
-    const long ro = (long)row * p.h;
-    const u32x4* x = reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.x) + ro);
-    const u32x4* ga = reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.ga) + ro);
-    const u32x4* gb = p.gb ? reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.gb) + ro) : nullptr;
-    const u32x4* dres = p.dres ? reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.dres) + ro) : nullptr;
-    u32x4* dx = reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.dx) + ro);
-    const float mean = RMS ? 0.0f : p.mean[row];
-    const float rstd = p.rstd[row];
-
-    u32x4 xs[NC], gs[NC];
+  const int r0 = blockIdx.x * rows_per_block, r1 = min(p.rows, r0 + rows_per_block);
+  int buf = 0;
+  for (int rb = r0; rb < r1; rb += R, buf ^= 1) {
+    u32x4 xs[R], gs[R], bs[R], ds[R];
+    float mean[R], rstd[R];
 #pragma unroll
-    for (int i = 0; i < NC; ++i) {
-      const int c = lane + 64 * i;
-      u32x4 z = {0u, 0u, 0u, 0u};
-      xs[i] = c < nch ? x[c] : z;
-      gs[i] = c < nch ? ga[c] : z;
+    for (int j = 0; j < R; ++j) {
+      const int row = rb + j;
+      const bool ok = live && row < r1;
+      const long at = (long)row * p.h + tid * 8;
+      xs[j] = ok ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.x) + at) : zero4;
+      gs[j] = ok ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.ga) + at) : zero4;
+      bs[j] = (ok && p.gb) ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.gb) + at) : zero4;
+      ds[j] = (ok && p.dres) ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.dres) + at) : zero4;
+      mean[j] = (!RMS && row < r1) ? p.mean[row] : 0.0f;
+      rstd[j] = row < r1 ? p.rstd[row] : 0.0f;
     }
-    if (gb) {
+    float gv[R][8], sums[2 * R];
 #pragma unroll
-      for (int i = 0; i < NC; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nch) {
-          float f[8], g[8];
-          unpack8(gs[i], f); unpack8(gb[c], g);
+    for (int j = 0; j < R; ++j) {
+      float xv[8], bv[8];
+      unpack8(xs[j], xv); unpack8(gs[j], gv[j]); unpack8(bs[j], bv);
+      float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] += g[e];
-          gs[i] = pack8(f);
-        }
+      for (int e = 0; e < 8; ++e) {
+        gv[j][e] += bv[e];
+        const float xh = (xv[e] - mean[j]) * rstd[j];
+        const float dxh = gv[j][e] * gm[e];
+        s1 += dxh;
+        s2 += dxh * xh;
+        dg[e] += gv[j][e] * xh;
+        if (!RMS) db[e] += gv[j][e];
       }
+      sums[2 * j] = RMS ? 0.0f : wave_sum(s1);
+      sums[2 * j + 1] = wave_sum(s2);
     }
-    float s1 = 0.0f, s2 = 0.0f;
+    if (lane == 0) {
 #pragma unroll
-    for (int i = 0; i < NC; ++i) {
-      const int c = lane + 64 * i;
-      if (c < nch) {
-        float xv[8], gv[8], gm[8];
-        unpack8(xs[i], xv); unpack8(gs[i], gv); unpack8(gam[c], gm);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float xh = (xv[e] - mean) * rstd;
-          const float dxh = gv[e] * gm[e];
-          s1 += dxh;
-          s2 += dxh * xh;
-          dg[i][e] += gv[e] * xh;
-          if (!RMS) db[i][e] += gv[e];
-        }
-      }
-    }
-    const float c1 = RMS ? 0.0f : wave_sum(s1) * inv_h;
-    const float c2 = wave_sum(s2) * inv_h;
-#pragma unroll
-    for (int i = 0; i < NC; ++i) {
-      const int c = lane + 64 * i;
-      if (c < nch) {
-        float xv[8], gv[8], gm[8], o[8];
-        unpack8(xs[i], xv); unpack8(gs[i], gv); unpack8(gam[c], gm);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float xh = (xv[e] - mean) * rstd;
-          o[e] = rstd * (gv[e] * gm[e] - c1 - xh * c2);
-        }
-        if (dres) {
-          float r[8]; unpack8(dres[c], r);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] += r[e];
-        }
-        dx[c] = pack8(o);
-      }
-    }
-  }
-
-  // combine the 4 waves in order 0,1,2,3 and write this workgroup's partial row
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
-#pragma unroll
-      for (int i = 0; i < NC; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nch) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int col = c * 8 + e;
-            if (w == 0) { red[col] = dg[i][e]; if (!RMS) red[p.h + col] = db[i][e]; }
-            else { red[col] += dg[i][e]; if (!RMS) red[p.h + col] += db[i][e]; }
-          }
-        }
-      }
+      for (int k = 0; k < 2 * R; ++k) red[buf][wave][k] = sums[k];
     }
     __syncthreads();
+    float tot[2 * R];
+#pragma unroll
+    for (int k = 0; k < 2 * R; ++k) tot[k] = 0.0f;
+    for (int w = 0; w < nw; ++w) {
+#pragma unroll
+      for (int k4 = 0; k4 < 2 * R; k4 += 4) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(&red[buf][w][k4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tot[k4 + e] += t[e];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      const int row = rb + j;
+      if (live && row < r1) {
+        const float c1 = tot[2 * j] * inv_h, c2 = tot[2 * j + 1] * inv_h;
+        float o[8], rv[8], xv[8];
+        unpack8(ds[j], rv); unpack8(xs[j], xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          o[e] = rstd[j] * (gv[j][e] * gm[e] - c1 - (xv[e] - mean[j]) * rstd[j] * c2) + rv[e];
+        *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.dx) + (long)row * p.h + tid * 8) = pack8(o);
+      }
+    }
   }
-  float* pg = p.part_g + (long)blockIdx.x * p.h;
-  float* pb = RMS ? nullptr : p.part_b + (long)blockIdx.x * p.h;
-  for (int col = threadIdx.x; col < p.h; col += 256) {
-    pg[col] = red[col];
-    if (!RMS) pb[col] = red[p.h + col];
+  if (live) {
+    f32x4* pg = reinterpret_cast<f32x4*>(p.part_g + (long)blockIdx.x * p.h + tid * 8);
+    pg[0] = f32x4{dg[0], dg[1], dg[2], dg[3]};
+    pg[1] = f32x4{dg[4], dg[5], dg[6], dg[7]};
+    if (!RMS) {
+      f32x4* pb = reinterpret_cast<f32x4*>(p.part_b + (long)blockIdx.x * p.h + tid * 8);
+      pb[0] = f32x4{db[0], db[1], db[2], db[3]};
+      pb[1] = f32x4{db[4], db[5], db[6], db[7]};
+    }
   }
 }
 
-// out[col] (+)= sum_k part[k][col]: the second stage of every column reduction.  A workgroup owns 32
+// out[col] (+)= sum_k part[k][col]: the second stage of every column reduction, for up to
+// COLSUM_MAX_JOBS independent reductions in one launch (blockIdx.y = job).  A workgroup owns 32
 // columns; its 8 row groups each sum every 8th partial row, then the 8 group sums are added in
 // group order (a fixed summation tree: results do not depend on scheduling).
 __global__ __launch_bounds__(256)
-void colsum_finish_kernel(const float* __restrict__ part, int nparts, long stride, int n, float* __restrict__ out, int accumulate) {
+void colsum_finish_kernel(const ColsumJobs jobs, int accumulate) {
   __shared__ float red[8][32];
+  const ColsumJob job = jobs.job[blockIdx.y];
+  if ((int)blockIdx.x * 32 >= job.n) return;
   const int c = threadIdx.x & 31, kg = threadIdx.x >> 5;
   const int col = blockIdx.x * 32 + c;
   float s = 0.0f;
-  if (col < n) {
+  if (col < job.n) {
+    for (int g = 0; g < job.nouter; ++g) {
+      const float* part = job.part + (long)g * job.ostride + col;
 #pragma unroll 4
-    for (int k = kg; k < nparts; k += 8) s += part[(long)k * stride + col];
+      for (int k = kg; k < job.nparts; k += 8) s += part[(long)k * job.stride];
+    }
   }
   red[kg][c] = s;
   __syncthreads();
-  if (kg == 0 && col < n) {
+  if (kg == 0 && col < job.n) {
     float t = red[0][c];
 #pragma unroll
     for (int g = 1; g < 8; ++g) t += red[g][c];
-    out[col] = accumulate ? out[col] + t : t;
+    job.out[col] = accumulate ? job.out[col] + t : t;
   }
 }
 
@@ -290,33 +282,22 @@ hipError_t fwd_dispatch(const NormFwdArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int NC, bool RMS>
-hipError_t bwd_launch(const NormBwdArgs& a, int nblocks, hipStream_t st) {
-  auto kern = norm_bwd_kernel<NC, RMS>;
-  const int lds = 2 * a.h * (int)sizeof(float);
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  hipLaunchKernelGGL(kern, dim3(nblocks), dim3(256), lds, st, a);
-  return hipGetLastError();
-}
-
 template <bool RMS>
 hipError_t bwd_dispatch(const NormBwdArgs& a, int nblocks, hipStream_t st) {
-  const int nc = ((a.h >> 3) + 63) / 64;
-  if (nc <= 4) return bwd_launch<4, RMS>(a, nblocks, st);
-  if (nc <= 8) return bwd_launch<8, RMS>(a, nblocks, st);
-  if (nc <= 10) return bwd_launch<10, RMS>(a, nblocks, st);
-  return bwd_launch<MAXC, RMS>(a, nblocks, st);
+  const int nt = (((a.h >> 3) + 63) / 64) * 64;           // one thread per 16-byte chunk of a row
+  const int rpb = (a.rows + nblocks - 1) / nblocks;
+  const dim3 grid(nblocks), block(nt);
+  if (nt <= 256) hipLaunchKernelGGL((norm_bwd_kernel<256, 4, RMS>), grid, block, 0, st, a, rpb);
+  else if (nt <= 512) hipLaunchKernelGGL((norm_bwd_kernel<512, 4, RMS>), grid, block, 0, st, a, rpb);
+  else if (nt <= 768) hipLaunchKernelGGL((norm_bwd_kernel<768, 4, RMS>), grid, block, 0, st, a, rpb);
+  else hipLaunchKernelGGL((norm_bwd_kernel<1024, 2, RMS>), grid, block, 0, st, a, rpb);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 int norm_bwd_blocks(int rows) {
-  const int want = (rows + 3) / 4;
+  const int want = (rows + NORM_BWD_ROWS - 1) / NORM_BWD_ROWS;
   return want < NORM_BWD_MAX_BLOCKS ? want : NORM_BWD_MAX_BLOCKS;
 }
 
@@ -330,11 +311,17 @@ hipError_t norm_bwd_launch(const NormBwdArgs& a, hipStream_t st) {
 }
 
 hipError_t colsum_finish_launch(const float* part, int nparts, int n, float* out, int accumulate, hipStream_t st) {
-  return colsum_finish_strided_launch(part, nparts, n, n, out, accumulate, st);
+  ColsumJobs jobs{};
+  jobs.job[0] = {part, out, nparts, n, (long)n, 1, 0};
+  return colsum_finish_jobs_launch(jobs, 1, accumulate, st);
 }
 
-hipError_t colsum_finish_strided_launch(const float* part, int nparts, long stride, int n, float* out, int accumulate, hipStream_t st) {
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((n + 31) / 32), dim3(256), 0, st, part, nparts, stride, n, out, accumulate);
+hipError_t colsum_finish_jobs_launch(const ColsumJobs& jobs, int njobs, int accumulate, hipStream_t st) {
+  if (njobs <= 0) return hipSuccess;
+  if (njobs > COLSUM_MAX_JOBS) return hipErrorInvalidValue;
+  int widest = 0;
+  for (int k = 0; k < njobs; ++k) widest = jobs.job[k].n > widest ? jobs.job[k].n : widest;
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((widest + 31) / 32, njobs), dim3(256), 0, st, jobs, accumulate);
   return hipGetLastError();
 }
 

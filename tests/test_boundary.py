@@ -129,6 +129,6 @@ def test_single_kernel_entry_points_validate():
     assert lib.domino_norm_fwd(None, None, None, None, 1, None, None, 1, None, 1, 4, 16, 0, 1e-5, None) == domino.ERR_NULL_POINTER
     assert lib.domino_rope(1, 64, 4, 4, 0, 2, 1, 64, 10000.0, 0, None) == domino.ERR_INVALID_ARG   # blocks exceed ld
     assert lib.domino_colsum(1, 64, 4, 60, 1, 0, 1, None) == domino.ERR_UNSUPPORTED
-    assert lib.domino_norm_bwd_scratch_floats(2048, 5120) == 2 * 256 * 5120
+    assert lib.domino_norm_bwd_scratch_floats(2048, 5120) == 2 * 128 * 5120
     assert lib.domino_profile_classes() >= 18 and lib.domino_profile_name(1) == b"gemm_qkv"
     assert lib.domino_profile_read(99, None, None) == domino.ERR_INVALID_ARG
