@@ -17,6 +17,12 @@ import os
 import sys
 import time
 
+# The pool's streams only overlap if each has a hardware queue of its own; the HIP runtime's default of 4
+# queues per process leaves one of them to the null stream, and two pool streams then share a queue and
+# run their row slices one after the other.  Must be set before the runtime initialises (import torch).
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+
 BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 DEFAULT_WORKLOAD = "gpt3-13b"      # the shard the throughput target is quoted on
 
@@ -73,6 +79,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--graph", action="store_true", help="capture the step in a HIP graph and replay it")
     ap.add_argument("--p", type=int, default=None)
     ap.add_argument("--q", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -99,9 +106,20 @@ def main():
     buf = harness.LayerBuffers(sc, params, x, dy, others, nstreams=args.streams)
     s0 = buf.streams[0]
 
-    def step():
+    def eager_step():
         buf.forward()
         buf.backward(accumulate=False)
+
+    step = eager_step
+    if args.graph:
+        # one pass of the path captured once on streams[0] (the library forks the other streams from it
+        # and joins them back) and replayed: same kernels, launch order fixed by the graph's edges
+        eager_step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s0):
+            eager_step()
+        step = graph.replay
 
     for _ in range(args.warmup):
         step()

@@ -182,6 +182,13 @@ struct ProfScope {
   }
 };
 
+// row slices in flight at once in the layer call being enqueued (tile choice of its GEMMs); 1 outside
+thread_local int g_concurrency = 1;
+struct ConcurrencyScope {
+  explicit ConcurrencyScope(int c) { g_concurrency = c < 1 ? 1 : c; }
+  ~ConcurrencyScope() { g_concurrency = 1; }
+};
+
 inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 inline const char* at(const void* base, size_t off) { return static_cast<const char*>(base) + off; }
 inline char* at(void* base, size_t off) { return static_cast<char*>(base) + off; }
@@ -190,6 +197,7 @@ GemmArgs gemm_args(const void* A, long lda, const void* B, long ldb, void* C, lo
   GemmArgs a{};
   a.A = A; a.B = B; a.C = C; a.lda = lda; a.ldb = ldb; a.ldc = ldc; a.M = M; a.N = N; a.K = K;
   a.gelu_tanh = 1;
+  a.concurrency = g_concurrency;
   return a;
 }
 
@@ -278,6 +286,7 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
   g_sync_used = 0;
+  ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   const int ns = nstreams;
   hipStream_t s0 = as_stream(streams[0]);
@@ -402,6 +411,7 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
   g_sync_used = 0;
+  ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   const int ns = nstreams;
   hipStream_t s0 = as_stream(streams[0]);

@@ -23,10 +23,11 @@ struct GemmArgs {
   int n_split;           // SwiGLU: number of gate (= up) columns
   int beta;              // EPI_ACC_F32: 1 = accumulate into C
   int gelu_tanh;
+  int concurrency;       // launches of similar size expected in flight at once (other streams); 0 = 1
   int tiles_m, tiles_n;  // filled by the launcher
   long a_bytes, b_bytes; // extent of the A / B views in bytes, filled by the launcher
 };
 
-int gemm_pick_tile(int M, int N);
+int gemm_pick_tile(int M, int N, int concurrency);
 // tile_cfg < 0: pick by shape.  Enqueues on `stream`; returns the launch status.
 hipError_t gemm_launch(int layout, int epi, const GemmArgs& a, int tile_cfg, hipStream_t stream);

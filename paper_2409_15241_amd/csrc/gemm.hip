@@ -17,8 +17,9 @@
 // The MFMA is issued with the roles swapped (first operand = B fragment) so that a lane ends up
 // with 4 consecutive n for one m: 8-byte bf16 / 16-byte fp32 stores.
 #include "gemm.h"
-#include <cstdlib>
+#include <cmath>
 #include "lds_dma.h"
+#include <type_traits>
 
 namespace {
 
@@ -107,54 +108,67 @@ void gemm_kernel(const GemmArgs p) {
 
   const uint32_t smem_base = lds_addr(smem);
   const int fr = lane & 31, fh = lane >> 5;
+  constexpr int STEP_READS = (AKS ? 2 * TM : TM) + (BKS ? 2 * TN : TN);
+  static_assert(STEP_READS <= 15, "lgkmcnt is a 4-bit counter");
+  u32x4 fa[2][TM], fb[2][TN];
+  // fragments of MFMA step ks (16 contraction elements) of the stage at LDS address st
+  auto read_step = [&](auto ks_c, uint32_t st) {
+    constexpr int ks = decltype(ks_c)::value;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+      if constexpr (AKS) {
+        const u32x2 lo = ds_read_tr_at<0>(st + offA[ks][j]), hi = ds_read_tr_at<8 * BM>(st + offA[ks][j]);
+        fa[ks][j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+      } else {
+        fa[ks][j] = (j == 0) ? ds_read_b128_at<0>(st + offA[ks][0]) : (j == 1) ? ds_read_b128_at<2048>(st + offA[ks][0])
+                  : (j == 2) ? ds_read_b128_at<4096>(st + offA[ks][0]) : ds_read_b128_at<6144>(st + offA[ks][0]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      if constexpr (BKS) {
+        const u32x2 lo = ds_read_tr_at<0>(st + offB[ks][i]), hi = ds_read_tr_at<8 * BN>(st + offB[ks][i]);
+        fb[ks][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+      } else {
+        fb[ks][i] = (i == 0) ? ds_read_b128_at<0>(st + offB[ks][0]) : (i == 1) ? ds_read_b128_at<2048>(st + offB[ks][0])
+                  : (i == 2) ? ds_read_b128_at<4096>(st + offB[ks][0]) : ds_read_b128_at<6144>(st + offB[ks][0]);
+      }
+    }
+  };
+  // The MFMAs of step ks.  LDS returns in order, so after lgkmcnt(STEP_READS) only the younger step's
+  // reads may be outstanding.  The empty asm statements "use and define" the fragments so that no MFMA
+  // can be scheduled above the wait.
+  auto mma_step = [&](auto ks_c) {
+    constexpr int ks = decltype(ks_c)::value;
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(STEP_READS) : "memory");
+#pragma unroll
+    for (int j = 0; j < TM; ++j) asm volatile("" : "+v"(fa[ks][j]));
+#pragma unroll
+    for (int i = 0; i < TN; ++i) asm volatile("" : "+v"(fb[ks][i]));
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[ks][i]),
+                                                            __builtin_bit_cast(bf16x8, fa[ks][j]), acc[i][j], 0, 0, 0);
+  };
+  using step0 = std::integral_constant<int, 0>;
+  using step1 = std::integral_constant<int, 1>;
+
+  // Software pipeline over the 16-deep MFMA steps: the LDS reads of a step are in flight while the
+  // MFMAs of the step before run, across the tile boundary too (tile kt+1 must therefore have landed
+  // by the middle of tile kt: one tile less of HBM/L2 prefetch distance than the ring depth).
+  wait_vmcnt<(NST - 2) * LOADS_PER_TILE>();
+  __builtin_amdgcn_s_barrier();
+  read_step(step0{}, smem_base);
   for (int kt = 0; kt < nk; ++kt) {
-    wait_vmcnt<(NST - 2) * LOADS_PER_TILE>();      // tile kt has landed; the younger tiles may be in flight
-    __builtin_amdgcn_s_barrier();                  // ... for every wave; and stage (kt-1)%NST is free again
+    read_step(step1{}, smem_base + (kt % NST) * STAGE);
+    mma_step(step0{});
+    wait_vmcnt<(NST - 3) * LOADS_PER_TILE>();      // tile kt+1 has landed (this wave's share)
+    __builtin_amdgcn_s_barrier();                  // ... everybody's; and nobody reads stage (kt-1)%NST any more
     issue_tile(kt + NST - 1);
-    const uint32_t st = smem_base + (kt % NST) * STAGE;
-    u32x4 fa[2][TM], fb[2][TN];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-      for (int j = 0; j < TM; ++j) {
-        if constexpr (AKS) {
-          const u32x2 lo = ds_read_tr_at<0>(st + offA[ks][j]), hi = ds_read_tr_at<8 * BM>(st + offA[ks][j]);
-          fa[ks][j] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-        } else {
-          fa[ks][j] = (j == 0) ? ds_read_b128_at<0>(st + offA[ks][0]) : (j == 1) ? ds_read_b128_at<2048>(st + offA[ks][0])
-                    : (j == 2) ? ds_read_b128_at<4096>(st + offA[ks][0]) : ds_read_b128_at<6144>(st + offA[ks][0]);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < TN; ++i) {
-        if constexpr (BKS) {
-          const u32x2 lo = ds_read_tr_at<0>(st + offB[ks][i]), hi = ds_read_tr_at<8 * BN>(st + offB[ks][i]);
-          fb[ks][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-        } else {
-          fb[ks][i] = (i == 0) ? ds_read_b128_at<0>(st + offB[ks][0]) : (i == 1) ? ds_read_b128_at<2048>(st + offB[ks][0])
-                    : (i == 2) ? ds_read_b128_at<4096>(st + offB[ks][0]) : ds_read_b128_at<6144>(st + offB[ks][0]);
-        }
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      // LDS returns in order: after step 0's wait only step 1's reads may be outstanding.  The empty asm
-      // statements "use and define" the fragments so that no MFMA can be scheduled above the wait.
-      constexpr int STEP_READS = (AKS ? 2 * TM : TM) + (BKS ? 2 * TN : TN);
-      static_assert(STEP_READS <= 15, "lgkmcnt is a 4-bit counter");
-      if (ks == 0) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(STEP_READS) : "memory");
-      else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-      for (int j = 0; j < TM; ++j) asm volatile("" : "+v"(fa[ks][j]));
-#pragma unroll
-      for (int i = 0; i < TN; ++i) asm volatile("" : "+v"(fb[ks][i]));
-#pragma unroll
-      for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[ks][i]),
-                                                              __builtin_bit_cast(bf16x8, fa[ks][j]), acc[i][j], 0, 0, 0);
-    }
+    read_step(step0{}, smem_base + ((kt + 1) % NST) * STAGE);
+    mma_step(step1{});
   }
   wait_vmcnt<0>();     // the zero-fill loads issued past the last tile must land before the LDS is released
 
@@ -270,19 +284,41 @@ hipError_t launch_layout(const GemmArgs& a, int tile_cfg, hipStream_t stream) {
 
 }  // namespace
 
-int gemm_pick_tile(int M, int N) {
-  // One 128x128 workgroup already keeps a CU's MFMA pipes busy, and two fit per CU; the 256x256 tile
-  // halves the L2 -> LDS traffic per flop but only pays once there are several tiles per CU.
-  static const int policy = getenv("DOMINO_TILE_POLICY") ? atoi(getenv("DOMINO_TILE_POLICY")) : 0;
-  const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-  if (policy == 1 && M % 256 == 0 && N % 256 == 0) return GEMM_TILE_256x256;
-  if (policy == 2 && N % 256 == 0) return GEMM_TILE_128x256;
-  if (policy == 3 && M % 256 == 0) return GEMM_TILE_256x128;
-  return t256 >= 512 ? GEMM_TILE_256x256 : GEMM_TILE_128x128;
+int gemm_pick_tile(int M, int N, int concurrency) {
+  // The main loop is bound by the operand stream into LDS, so a workgroup's rate grows with the flops
+  // per operand byte of its tile, BM*BN/(BM+BN); the relative per-CU rates below are measured.
+  // Against that, one launch only fills the 256 CUs if it has enough tiles.  With three or more
+  // launches of this size in flight on other streams the chip is kept full dynamically and only the
+  // rate and the padding of ragged edges count; alone, whole rounds of tiles count.  128x128 tiles run
+  // two to a CU (sharing its feed) and balance dynamically.
+  if (concurrency < 1) concurrency = 1;
+  struct Cand { int id, bm, bn; double rate; };
+  static const Cand cands[] = {{GEMM_TILE_256x256, 256, 256, 6.3}, {GEMM_TILE_128x256, 128, 256, 4.5},
+                               {GEMM_TILE_256x128, 256, 128, 4.5}, {GEMM_TILE_128x128, 128, 128, 3.4}};
+  int best = GEMM_TILE_128x128;
+  double best_cost = 1e30;
+  for (const Cand& c : cands) {
+    const double tiles = (double)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+    double rounds, rate = c.rate;
+    if (concurrency >= 3) {
+      rounds = tiles / 256.0;
+    } else if (c.id == GEMM_TILE_128x128) {
+      const double t = tiles * concurrency;
+      if (t > 256) { rate = 2.1; rounds = t / 512 > 1.0 ? t / 512 : 1.0; }
+      else rounds = 1.0;
+    } else {
+      const double t = tiles * concurrency;
+      rounds = ceil(t / 256.0);
+      if (rounds > 2) rounds = t / 256.0 + 0.5;
+    }
+    const double cost = rounds * c.bm * c.bn / rate;
+    if (cost < best_cost * 0.999) { best_cost = cost; best = c.id; }
+  }
+  return best;
 }
 
 hipError_t gemm_launch(int layout, int epi, const GemmArgs& a, int tile_cfg, hipStream_t stream) {
-  if (tile_cfg < 0) tile_cfg = gemm_pick_tile(a.M, epi == EPI_SWIGLU ? 2 * a.n_split : a.N);
+  if (tile_cfg < 0) tile_cfg = gemm_pick_tile(a.M, epi == EPI_SWIGLU ? 2 * a.n_split : a.N, a.concurrency);
   if (layout == GEMM_NN) {
     switch (epi) {
       case EPI_STORE:     return launch_layout<false, true, EPI_STORE>(a, tile_cfg, stream);
