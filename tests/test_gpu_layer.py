@@ -57,9 +57,8 @@ def oracle(sc, params, x, dy, others):
 
 def check(got, F, B, tol=TOL, grad_scale=1.0):
     worst = {}
-    for k in ("attn_partial", "mlp_partial", "y", "x1", "ctx"):
+    for k in ("attn_partial", "mlp_partial", "y", "x1", "ctx", "lse"):
         worst[k] = relerr(got[k], F[k])
-    assert np.max(np.abs(got["lse"] - F["lse"])) < 2e-2
     for k in ("dln2_partial", "dln1_partial", "dx"):
         worst[k] = relerr(got[k], B[k])
     for k, g in B["grads"].items():
@@ -146,6 +145,17 @@ MID = [
 @pytest.mark.parametrize("sc", MID, ids=[m.name for m in MID])
 def test_mid_shapes_with_ragged_tiles(H, sc):
     case(H, sc, random_affine=True)
+
+
+FULL = [synth.WORKLOADS[n] for n in ("gpt3-13b", "llama2-7b")]
+
+
+@pytest.mark.parametrize("sc", FULL, ids=[m.name for m in FULL])
+def test_full_size_shard_in_the_benchmark_configuration(H, sc):
+    """The configured full-size shards (GPT-3 13B is the one bench.py times), on 4 streams as bench.py
+    launches them: every output and gradient element against the oracle, which finishes a full-size
+    layer in seconds."""
+    case(H, sc, random_affine=True, nstreams=4)
 
 
 def test_schedule_invariance_bitwise(H):
