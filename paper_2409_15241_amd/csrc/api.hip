@@ -290,16 +290,19 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
 
   const int ns = nstreams;
   hipStream_t s0 = as_stream(streams[0]);
+  const int nslice = L.p < ns ? L.p : ns;                  // streams that carry row slices
+  const bool wide = ns >= L.p * L.q;                        // enough streams for every column piece
+  auto piece_stream = [&](int i, int j) { return (wide && j > 0) ? i + j * L.p : i % nslice; };
   std::vector<char> used(ns, 0);
   for (int i = 0; i < L.p; ++i)
-    for (int j = 0; j < L.q; ++j) used[(i + j * L.p) % ns] = 1;
+    for (int j = 0; j < L.q; ++j) used[piece_stream(i, j)] = 1;
   for (int k = 1; k < ns; ++k)
     if (used[k]) TRY(edge(s0, as_stream(streams[k])));
 
   const int Ms = L.Ms;
   const bool rms = L.llama;
   for (int i = 0; i < L.p; ++i) {
-    hipStream_t st = as_stream(streams[i % ns]);
+    hipStream_t st = as_stream(streams[i % nslice]);
     const size_t r0 = (size_t)i * Ms;                       // first token row of the slice
     const size_t rh = r0 * L.h * 2;                         // byte offset into [M, h] bf16 tensors
     const char* xi = at(x, rh);
@@ -342,7 +345,7 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
     }
     // F4: (XA) * B_j, one piece per column slice, written in place into the full-width buffer
     for (int j = 0; j < L.q; ++j) {
-      hipStream_t sj = as_stream(streams[(i + j * L.p) % ns]);
+      hipStream_t sj = as_stream(streams[piece_stream(i, j)]);
       TRY(edge(st, sj));
       {
         ProfScope ps(PC_GEMM_OUT, sj);
@@ -368,7 +371,7 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
       else { a.bias = P->b_up; LAUNCH(gemm_launch(GEMM_NN, EPI_BIAS_GELU, a, -1, st), "mlp-up product"); }
     }
     for (int j = 0; j < L.q; ++j) {  // F7
-      hipStream_t sj = as_stream(streams[(i + j * L.p) % ns]);
+      hipStream_t sj = as_stream(streams[piece_stream(i, j)]);
       TRY(edge(st, sj));
       {
         ProfScope ps(PC_GEMM_DOWN, sj);

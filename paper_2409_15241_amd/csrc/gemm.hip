@@ -171,6 +171,13 @@ void gemm_kernel(const GemmArgs p) {
     mma_step(step1{});
   }
   wait_vmcnt<0>();     // the zero-fill loads issued past the last tile must land before the LDS is released
+  // The last iteration's look-ahead reads are still in flight: they must land in their registers
+  // before the epilogue may reuse those registers.
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int j = 0; j < TM; ++j) asm volatile("" : "+v"(fa[0][j]));
+#pragma unroll
+  for (int i = 0; i < TN; ++i) asm volatile("" : "+v"(fb[0][i]));
 
   // ---- epilogue: accumulator (i, j) value v is C[m][n] with
   //      m = m0 + wm0 + 32 j + lane%32,  n = n0 + wn0 + 32 i + 8 (v/4) + 4 (lane/32) + v%4

@@ -55,6 +55,9 @@ class LayerBuffers:
                       for k, v in self.params.items()}
         # fixed pool of streams created once and picked by index (default priority)
         self.streams = [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
+        # the uploads and fills above were enqueued on torch's current stream, which the pool's streams
+        # do not wait for: everything must have landed before the first library call reads it
+        torch.cuda.synchronize(dev)
 
     def forward(self) -> None:
         domino.domino_layer_fwd(self.cfg, self.params, self.x, self.attn_others, self.mlp_others,

@@ -176,6 +176,29 @@ def test_schedule_invariance_bitwise(H):
             np.testing.assert_array_equal(g, c["grads"][k], err_msg=k)
 
 
+@pytest.mark.parametrize("nstreams", [2, 4])
+def test_repeated_steps_are_bitwise_identical(H, nstreams):
+    """The same step on the same buffers, many times while other slices' kernels share the CUs: every
+    repetition gives the bits of the first (no value may depend on the timing of a look-ahead read or
+    of another stream)."""
+    sc = MID[2]
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    buf = H.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=nstreams)
+    first = None
+    for rep in range(40):
+        buf.forward()
+        buf.backward(accumulate=False)
+        buf.sync()
+        cur = {k: g.clone() for k, g in buf.grads.items() if g is not None}
+        cur.update(y=buf.y.clone(), dx=buf.dx.clone(), dln1=buf.dln1_partial.clone(), dln2=buf.dln2_partial.clone())
+        if first is None:
+            first = cur
+            continue
+        diff = [k for k in cur if not torch.equal(cur[k], first[k])]
+        assert not diff, f"repetition {rep} differs from the first in {diff}"
+
+
 def test_accumulate_adds_to_existing_gradients(H):
     sc = TINY
     params = synth.make_rank_params(sc, random_affine=True)
