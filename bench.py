@@ -48,6 +48,23 @@ def algorithmic_flops(sc):
     return 3.0 * (gemm + attn)
 
 
+TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_per_launch.md")
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE runs (lines
+    'traffic[<workload>][<kernel>] = <bytes>' of the summary file), or None if it holds no such line."""
+    key = f"traffic[{workload}][{kernel}] ="
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            for ln in fh:
+                if ln.startswith(key):
+                    return float(ln[len(key):].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(sc, budget_s=30.0):
     """The oracle as it stands, on the host cores, on one row slice of the same workload."""
     import numpy as np
@@ -85,6 +102,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-step-class timing table to stderr")
+    ap.add_argument("--copy-check", type=int, default=0, metavar="MIB",
+                    help="also run three plain device copies of this many MiB (a kernel of known HBM traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters against)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is the one-GPU rank-local path; run it with --gpus 1 "
@@ -111,6 +131,10 @@ def main():
         buf.backward(accumulate=False)
 
     step = eager_step
+    if args.graph and args.streams not in (2, 4):
+        print("bench.py: --graph is limited to pools of 2 or 4 streams (graph instantiation of the other pool "
+              "sizes crashed inside the runtime on this ROCm)", file=sys.stderr)
+        sys.exit(2)
     if args.graph:
         # one pass of the path captured once on streams[0] (the library forks the other streams from it
         # and joins them back) and replayed: same kernels, launch order fixed by the graph's edges
@@ -186,7 +210,8 @@ def main():
         avg_ms = tot / n
         achieved = f / (tot * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                    "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                    "traffic": measured_traffic(sc.name, dom_name),
                     "avg_launch_us": avg_ms * 1e3, "launches_per_step": n // args.steps,
                     "flops_per_launch": f / n, "ms_per_step_instrumented": inst_ms}
         if args.breakdown:
@@ -194,6 +219,13 @@ def main():
             for k, (t, m) in sorted(table.items(), key=lambda kv: -kv[1][0]):
                 tf = per[k] / (t / m * 1e-3) / 1e12 if k in per else float("nan")
                 print(f"{k:14s} {m // args.steps:11d} {t / m * 1e3:10.1f} {t / args.steps:8.3f} {tf:8.1f}", file=sys.stderr)
+
+    if args.copy_check:
+        src = torch.empty(args.copy_check << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(sc)
 
