@@ -25,6 +25,7 @@ struct GemmArgs {
   int gelu_tanh;
   int concurrency;       // launches of similar size expected in flight at once (other streams); 0 = 1
   int tiles_m, tiles_n;  // filled by the launcher
+  int group_m;           // filled by the launcher: tile rows per band of the XCD-blocked order, 0 = linear
   long a_bytes, b_bytes; // extent of the A / B views in bytes, filled by the launcher
 };
 
