@@ -296,8 +296,13 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
   std::vector<char> used(ns, 0);
   for (int i = 0; i < L.p; ++i)
     for (int j = 0; j < L.q; ++j) used[piece_stream(i, j)] = 1;
-  for (int k = 1; k < ns; ++k)
-    if (used[k]) TRY(edge(s0, as_stream(streams[k])));
+  {  // fork: one event on streams[0], every other stream of this call waits for it
+    hipEvent_t fork;
+    TRY(next_sync_event(&fork));
+    HIP_TRY(hipEventRecord(fork, s0), "hipEventRecord");
+    for (int k = 1; k < ns; ++k)
+      if (used[k]) HIP_TRY(hipStreamWaitEvent(as_stream(streams[k]), fork, 0), "hipStreamWaitEvent");
+  }
 
   const int Ms = L.Ms;
   const bool rms = L.llama;
@@ -419,7 +424,12 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
   const int ns = nstreams;
   hipStream_t s0 = as_stream(streams[0]);
   const int nused = L.p < ns ? L.p : ns;
-  for (int k = 1; k < nused; ++k) TRY(edge(s0, as_stream(streams[k])));
+  {  // fork: one event on streams[0], every other slice stream waits for it
+    hipEvent_t fork;
+    TRY(next_sync_event(&fork));
+    HIP_TRY(hipEventRecord(fork, s0), "hipEventRecord");
+    for (int k = 1; k < nused; ++k) HIP_TRY(hipStreamWaitEvent(as_stream(streams[k]), fork, 0), "hipStreamWaitEvent");
+  }
 
   const int Ms = L.Ms;
   const bool rms = L.llama;
