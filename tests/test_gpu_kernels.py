@@ -45,7 +45,7 @@ BF16_OUT = 6e-3     # one output rounding (2^-9 = 2e-3) plus bf16-rounded interm
 SHAPES = [(328, 200, 328), (256, 256, 64), (520, 776, 1376), (64, 2752 // 2, 192)]
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_gemm_nn_store_bias(dom, tile, M, N, K):
     rng = np.random.default_rng(M * 7 + N * 3 + K + tile)
@@ -78,7 +78,7 @@ def test_gemm_nn_writes_a_column_slice_in_place(dom):
 
 
 @pytest.mark.parametrize("tanh", [1, 0])
-@pytest.mark.parametrize("tile", [0, 2])
+@pytest.mark.parametrize("tile", [0, 2, 3])
 def test_gemm_nn_bias_gelu(dom, tile, tanh):
     rng = np.random.default_rng(11 + tile)
     M, N, K = 328, 264, 200
@@ -93,7 +93,7 @@ def test_gemm_nn_bias_gelu(dom, tile, tanh):
     assert relerr(host(Cd), O.gelu(ref_pre, bool(tanh))) < BF16_OUT
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
 @pytest.mark.parametrize("fl", [352, 96, 1376])
 def test_gemm_nn_swiglu(dom, tile, fl):
     rng = np.random.default_rng(13 + tile + fl)
@@ -109,7 +109,7 @@ def test_gemm_nn_swiglu(dom, tile, fl):
     assert relerr(host(act), O.silu(ref[:, :fl]) * ref[:, fl:]) < BF16_OUT
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
 @pytest.mark.parametrize("M,N,K", SHAPES)
 def test_gemm_nt_input_gradient(dom, tile, M, N, K):
     rng = np.random.default_rng(M + N + K + 17 * tile)
@@ -147,7 +147,7 @@ def test_gemm_nt_swiglu_backward(dom):
     assert relerr(host(Cd), ref) < BF16_OUT
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
 @pytest.mark.parametrize("M,N,K", [(328, 200, 328), (640, 520, 2048), (136, 1376, 264)])
 def test_gemm_tn_weight_gradient_accumulates(dom, tile, M, N, K):
     rng = np.random.default_rng(M + 2 * N + 3 * K + tile)
