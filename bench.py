@@ -227,6 +227,25 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    if roofline is not None and roofline["kernel"].startswith("gemm_kernel<TN"):
+        # context for `achieved`: the same launches with the chip to themselves (one stream, nothing else running)
+        Ms = sc.tokens // sc.p
+        shapes = [(sc.f_local, sc.hidden), (sc.hidden, sc.up_cols), (sc.h_local, sc.hidden), (sc.hidden, 3 * sc.h_local)]
+        tile = 2 if min(args.streams, sc.p) >= 3 else -1       # the tile the layer call picks
+        tot_ms, tot_fl = 0.0, 0.0
+        for (Mw, Nw) in shapes:
+            A = torch.randn(Ms, Mw, device="cuda").to(torch.bfloat16)
+            B = torch.randn(Ms, Nw, device="cuda").to(torch.bfloat16)
+            Cw = torch.zeros(Mw, Nw, device="cuda", dtype=torch.float32)
+            torch.cuda.synchronize()
+            run = lambda: domino.domino_gemm(domino.GEMM_TN, domino.EPI_ACC_F32, tile, A, Mw, B, Nw, Cw, Nw, Mw, Nw, Ms,
+                                             beta=1, stream=s0)
+            run()
+            tot_ms += timed(run, 10)
+            tot_fl += 2.0 * Ms * Mw * Nw
+        roofline["achieved_alone"] = tot_fl / (tot_ms * 1e-3) / 1e12
+        roofline["frac_alone"] = roofline["achieved_alone"] / BF16_MFMA_PEAK_TFLOPS
+
     cpu = None if args.no_cpu_baseline else cpu_baseline(sc)
 
     line = {
