@@ -132,3 +132,12 @@ def test_single_kernel_entry_points_validate():
     assert lib.domino_norm_bwd_scratch_floats(2048, 5120) == 2 * 128 * 5120
     assert lib.domino_profile_classes() >= 18 and lib.domino_profile_name(1) == b"gemm_qkv"
     assert lib.domino_profile_read(99, None, None) == domino.ERR_INVALID_ARG
+
+
+def test_tuner_candidates_cut_exactly():
+    from paper_2409_15241_amd import synth, tune
+    sc = synth.WORKLOADS["gpt3-13b"]
+    pairs = tune.candidates(sc)
+    assert (4, 2) in pairs and (1, 1) in pairs
+    assert all(sc.batch % p == 0 and sc.hidden % q == 0 for p, q in pairs)
+    assert (8, 1) not in pairs          # batch 4 cannot be cut into 8 row slices

@@ -206,3 +206,10 @@ def test_accumulate_adds_to_existing_gradients(H):
     got = run_gpu(H, sc, params, x, dy, None, accumulate_twice=True)
     F, B = oracle(sc, params, x, dy, None)
     check(got, F, B, grad_scale=2.0)
+
+
+def test_grid_search_returns_a_measured_setting(H):
+    from paper_2409_15241_amd import tune
+    best, table = tune.tune(TINY, pairs=[(1, 1), (2, 2)], streams=(1, 2), steps=2, warmup=1)
+    assert best in table and best[3] > 0.0
+    assert {(p, q) for p, q, _, _ in table} == {(1, 1), (2, 2)}
