@@ -322,7 +322,10 @@ int gemm_pick_tile(int M, int N, int concurrency) {
     const double tiles = (double)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
     double rounds, rate = c.rate;
     if (concurrency >= 3) {
-      rounds = tiles / 256.0;
+      // a launch of very few tiles is a long serial kernel on its stream's critical path: charge a
+      // tile shape for leaving most of a fair share of the chip (256 / concurrency CUs) unused
+      const double share = 256.0 / concurrency;
+      rounds = tiles / 256.0 * (tiles < share ? share / tiles : 1.0);
     } else if (c.id == GEMM_TILE_128x128) {
       const double t = tiles * concurrency;
       if (t > 256) { rate = 2.1; rounds = t / 512 > 1.0 ? t / 512 : 1.0; }
