@@ -115,7 +115,8 @@ int validate(const domino_cfg* c, Layout* L) {
   l.dot = take((size_t)l.b * l.nl * l.s * 4);
   {
     const int nb = norm_bwd_blocks(l.Ms);
-    const int rows[NAREAS] = {nb, nb, nb, nb, COLSUM_PARTS, COLSUM_PARTS, COLSUM_PARTS, COLSUM_PARTS};
+    // b_o and b_down come out of the Norm2 backward kernel (one partial row per workgroup), the others from column-sum passes
+    const int rows[NAREAS] = {nb, nb, nb, nb, COLSUM_PARTS, nb, COLSUM_PARTS, nb};
     const int width[NAREAS] = {l.h, l.h, l.h, l.h, 3 * l.hl, l.h, l.fl, l.h};
     size_t fo = 0;
     for (int k = 0; k < NAREAS; ++k) {
@@ -483,11 +484,12 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
       return DOMINO_OK;
     };
     auto norm_bwd = [&](const void* ga, const void* gb, const void* xin, const void* gamma, const float* mean,
-                        const float* rstd, const void* dres, void* out, int kg, int kb) -> int {
+                        const float* rstd, const void* dres, void* out, int kg, int kb, int kres = -1, int kdx = -1) -> int {
       ProfScope ps(PC_NORM_BWD, st);
       NormBwdArgs a{};
       a.ga = ga; a.gb = gb; a.x = xin; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dres = dres; a.dx = out;
       a.part_g = area(kg); a.part_b = area(kb); a.rows = Ms; a.h = L.h; a.rms = rms;
+      if (kres >= 0) { a.part_dres = area(kres); a.part_dx = area(kdx); }   // bias gradients of the two row-cut products
       LAUNCH(norm_bwd_launch(a, st), "norm backward");
       return DOMINO_OK;
     };
@@ -500,7 +502,6 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
       else LAUNCH(gemm_launch(GEMM_NT, EPI_DGELU, a, -1, st), "mlp-down input gradient");
     }
     TRY(wgrad(0, PC_WGRAD_DOWN, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
-    if (!L.llama) TRY(colsum(dyi, L.h, L.h, AREA_BDOWN));
     {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
       ProfScope ps(PC_DGRAD_UP, st);
       GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(dln2_partial, rh), L.h, Ms, L.h, L.upc);
@@ -510,14 +511,13 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
     if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, AREA_BUP));
     // B5
     TRY(norm_bwd(at(dln2_partial, rh), dln2_others ? at(dln2_others, rh) : nullptr, x1, P->norm2_g, mean2, rstd2,
-                 dyi, dx1, AREA_G2, AREA_B2));
+                 dyi, dx1, AREA_G2, AREA_B2, L.llama ? -1 : AREA_BDOWN, L.llama ? -1 : AREA_BO));
     {  // B6
       ProfScope ps(PC_DGRAD_OUT, st);
       GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
       LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "out-projection input gradient");
     }
     TRY(wgrad(2, PC_WGRAD_OUT, ctx, L.hl, dx1, L.h, G->w_o, L.h, L.hl, L.h));
-    if (!L.llama) TRY(colsum(dx1, L.h, L.h, AREA_BO));
     {  // B7
       ProfScope ps(PC_ATTN_BWD, st);
       AttnArgs a{};

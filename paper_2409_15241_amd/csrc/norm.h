@@ -32,6 +32,8 @@ struct NormBwdArgs {
   void* dx;               // bf16 [rows, h] = dres + NormBwd(ga + gb)
   float* part_g;          // fp32 [norm_bwd_blocks(rows), h]
   float* part_b;          // fp32 [norm_bwd_blocks(rows), h] (LayerNorm only)
+  float* part_dres;       // fp32 [norm_bwd_blocks(rows), h] or null: partial column sums of dres (a bias gradient)
+  float* part_dx;         // fp32 [norm_bwd_blocks(rows), h] or null: partial column sums of dx (a bias gradient)
   int rows, h, rms;
 };
 

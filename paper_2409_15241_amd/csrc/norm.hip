@@ -126,7 +126,7 @@ void norm_fwd_kernel(const NormFwdArgs p) {
 // registers and every load of an iteration (R rows x up to 4 tensors) is in flight at once.  The two
 // row sums cross the waves through LDS: wave sums in a double-buffered table, one barrier per
 // iteration, added in wave order (fixed summation order).
-template <int NT, int R, bool RMS>
+template <int NT, int R, bool RMS, bool SUMS>
 __global__ __launch_bounds__(NT)
 void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
   constexpr int NW = NT / 64;
@@ -140,9 +140,9 @@ void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
 
   float gm[8];
   unpack8(live ? reinterpret_cast<const u32x4*>(p.gamma)[tid] : zero4, gm);
-  float dg[8], db[8];
+  float dg[8], db[8], sres[8], sdx[8];     // sres / sdx: column sums of dres and of dx (SUMS only)
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { dg[e] = 0.0f; db[e] = 0.0f; }
+  for (int e = 0; e < 8; ++e) { dg[e] = 0.0f; db[e] = 0.0f; sres[e] = 0.0f; sdx[e] = 0.0f; }
 
   const int r0 = blockIdx.x * rows_per_block, r1 = min(p.rows, r0 + rows_per_block);
   int buf = 0;
@@ -204,8 +204,10 @@ void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
         float o[8], rv[8], xv[8];
         unpack8(ds[j], rv); unpack8(xs[j], xv);
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int e = 0; e < 8; ++e) {
           o[e] = rstd[j] * (gv[j][e] * gm[e] - c1 - (xv[e] - mean[j]) * rstd[j] * c2) + rv[e];
+          if (SUMS) { sres[e] += rv[e]; sdx[e] += o[e]; }
+        }
         *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.dx) + (long)row * p.h + tid * 8) = pack8(o);
       }
     }
@@ -218,6 +220,14 @@ void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
       f32x4* pb = reinterpret_cast<f32x4*>(p.part_b + (long)blockIdx.x * p.h + tid * 8);
       pb[0] = f32x4{db[0], db[1], db[2], db[3]};
       pb[1] = f32x4{db[4], db[5], db[6], db[7]};
+    }
+    if (SUMS) {
+      f32x4* pr = reinterpret_cast<f32x4*>(p.part_dres + (long)blockIdx.x * p.h + tid * 8);
+      pr[0] = f32x4{sres[0], sres[1], sres[2], sres[3]};
+      pr[1] = f32x4{sres[4], sres[5], sres[6], sres[7]};
+      f32x4* px = reinterpret_cast<f32x4*>(p.part_dx + (long)blockIdx.x * p.h + tid * 8);
+      px[0] = f32x4{sdx[0], sdx[1], sdx[2], sdx[3]};
+      px[1] = f32x4{sdx[4], sdx[5], sdx[6], sdx[7]};
     }
   }
 }
@@ -282,15 +292,16 @@ hipError_t fwd_dispatch(const NormFwdArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool RMS>
+template <bool RMS, bool SUMS>
 hipError_t bwd_dispatch(const NormBwdArgs& a, int nblocks, hipStream_t st) {
   const int nt = (((a.h >> 3) + 63) / 64) * 64;           // one thread per 16-byte chunk of a row
   const int rpb = (a.rows + nblocks - 1) / nblocks;
   const dim3 grid(nblocks), block(nt);
-  if (nt <= 256) hipLaunchKernelGGL((norm_bwd_kernel<256, 4, RMS>), grid, block, 0, st, a, rpb);
-  else if (nt <= 512) hipLaunchKernelGGL((norm_bwd_kernel<512, 4, RMS>), grid, block, 0, st, a, rpb);
-  else if (nt <= 768) hipLaunchKernelGGL((norm_bwd_kernel<768, 4, RMS>), grid, block, 0, st, a, rpb);
-  else hipLaunchKernelGGL((norm_bwd_kernel<1024, 2, RMS>), grid, block, 0, st, a, rpb);
+  constexpr int RW = SUMS ? 2 : 4;                        // rows per iteration where registers are tight
+  if (nt <= 256) hipLaunchKernelGGL((norm_bwd_kernel<256, 4, RMS, SUMS>), grid, block, 0, st, a, rpb);
+  else if (nt <= 512) hipLaunchKernelGGL((norm_bwd_kernel<512, 4, RMS, SUMS>), grid, block, 0, st, a, rpb);
+  else if (nt <= 768) hipLaunchKernelGGL((norm_bwd_kernel<768, RW, RMS, SUMS>), grid, block, 0, st, a, rpb);
+  else hipLaunchKernelGGL((norm_bwd_kernel<1024, 2, RMS, SUMS>), grid, block, 0, st, a, rpb);
   return hipGetLastError();
 }
 
@@ -307,7 +318,9 @@ hipError_t norm_fwd_launch(const NormFwdArgs& a, hipStream_t st) {
 
 hipError_t norm_bwd_launch(const NormBwdArgs& a, hipStream_t st) {
   const int nb = norm_bwd_blocks(a.rows);
-  return a.rms ? bwd_dispatch<true>(a, nb, st) : bwd_dispatch<false>(a, nb, st);
+  const bool sums = a.part_dres && a.part_dx && a.dres;
+  if (a.rms) return sums ? bwd_dispatch<true, true>(a, nb, st) : bwd_dispatch<true, false>(a, nb, st);
+  return sums ? bwd_dispatch<false, true>(a, nb, st) : bwd_dispatch<false, false>(a, nb, st);
 }
 
 hipError_t colsum_finish_launch(const float* part, int nparts, int n, float* out, int accumulate, hipStream_t st) {
