@@ -405,15 +405,13 @@ constexpr int RM_TILE = 16384;
 
 // ------------------------------------------------------------------------------------- dQ pass
 template <int D>
-__global__ __launch_bounds__(256)
-void attn_bwd_dq_kernel(const AttnArgs p) {
+DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
   using X = Dims<D>;
   constexpr int STAGE = 2 * RM_TILE;                      // K tile, V tile (64 keys each)
-  extern __shared__ __align__(1024) uint8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int qb = nxb - 1 - xb;
   const int hh = blockIdx.y, bi = blockIdx.z;
   const int s = p.seq;
   const int qw0 = qb * 128 + wave * 32, qpos = qw0 + fr;
@@ -485,15 +483,13 @@ void attn_bwd_dq_kernel(const AttnArgs p) {
 
 // ------------------------------------------------------------------------------------- dK / dV pass
 template <int D>
-__global__ __launch_bounds__(256)
-void attn_bwd_dkv_kernel(const AttnArgs p) {
+DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
   using X = Dims<D>;
   constexpr int STAGE = 2 * RM_TILE + 512;                // Q tile, dO tile (64 queries), lse[64], dot[64]
-  extern __shared__ __align__(1024) uint8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  const int kb = blockIdx.x;                              // 128 keys per workgroup
+  const int kb = xb;                              // 128 keys per workgroup
   const int hh = blockIdx.y, bi = blockIdx.z;
   const int s = p.seq;
   const int kw0 = kb * 128 + wave * 32, kpos = kw0 + fr;
@@ -586,6 +582,20 @@ void attn_bwd_dkv_kernel(const AttnArgs p) {
   }
 }
 
+
+// Both backward passes in one launch: workgroups [0, nxb) take the dK/dV pass of key block x (the longest
+// first), workgroups [nxb, 2 nxb) the dQ pass; the two are independent given D, so one launch puts twice
+// as many workgroups on the chip and the attention backward leaves its slice's critical path sooner.
+template <int D>
+__global__ __launch_bounds__(256)
+void attn_bwd_kernel(const AttnArgs p) {
+  extern __shared__ __align__(1024) uint8_t smem[];
+  const int nxb = gridDim.x >> 1;
+  const int xb = __builtin_amdgcn_readfirstlane(blockIdx.x);
+  if (xb < nxb) attn_bwd_dkv_body<D>(p, smem, xb);
+  else attn_bwd_dq_body<D>(p, smem, xb - nxb, nxb);
+}
+
 template <class K>
 hipError_t set_lds(K kern, int bytes, bool& done) {
   if (done) return hipSuccess;
@@ -612,15 +622,11 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t st) {
                      a.heads, D, a.dot);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  constexpr int LDS_Q = 2 * 2 * RM_TILE;
-  constexpr int LDS_KV = 2 * (2 * RM_TILE + 512);
-  static bool done_q = false, done_kv = false;
-  if ((e = set_lds(attn_bwd_dq_kernel<D>, LDS_Q, done_q)) != hipSuccess) return e;
-  if ((e = set_lds(attn_bwd_dkv_kernel<D>, LDS_KV, done_kv)) != hipSuccess) return e;
-  const dim3 grid((a.seq + 127) / 128, a.heads, a.batch);
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<D>, grid, dim3(256), LDS_KV, st, a);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<D>, grid, dim3(256), LDS_Q, st, a);
+  constexpr int LDS = 2 * (2 * RM_TILE + 512);             // the larger of the two passes' needs
+  static bool done = false;
+  if ((e = set_lds(attn_bwd_kernel<D>, LDS, done)) != hipSuccess) return e;
+  const dim3 grid(2 * ((a.seq + 127) / 128), a.heads, a.batch);
+  hipLaunchKernelGGL(attn_bwd_kernel<D>, grid, dim3(256), LDS, st, a);
   return hipGetLastError();
 }
 
