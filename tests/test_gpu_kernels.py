@@ -42,7 +42,7 @@ def relerr(got, ref):
 
 
 BF16_OUT = 6e-3     # one output rounding (2^-9 = 2e-3) plus bf16-rounded intermediates feeding nonlinearities
-SHAPES = [(328, 200, 328), (256, 256, 64), (520, 776, 1376), (64, 2752 // 2, 192)]
+SHAPES = [(328, 200, 328), (256, 256, 64), (520, 776, 1376), (64, 2752 // 2, 192), (8, 8, 8)]   # last: the smallest legal problem
 
 
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
@@ -164,7 +164,7 @@ def test_gemm_tn_weight_gradient_accumulates(dom, tile, M, N, K):
 
 
 @pytest.mark.parametrize("rms", [0, 1])
-@pytest.mark.parametrize("h", [256, 2560, 4096, 5120])
+@pytest.mark.parametrize("h", [8, 256, 2560, 4096, 5120, 8192])      # 8 and 8192: the narrowest and widest rows accepted
 def test_norm_forward(dom, rms, h):
     rng = np.random.default_rng(h + rms)
     rows, eps = 37, 1e-5
@@ -193,7 +193,7 @@ def test_norm_forward(dom, rms, h):
 
 
 @pytest.mark.parametrize("rms", [0, 1])
-@pytest.mark.parametrize("rows,h", [(37, 256), (1100, 2560), (300, 5120)])
+@pytest.mark.parametrize("rows,h", [(37, 256), (1100, 2560), (300, 5120), (1, 8), (19, 8192)])
 def test_norm_backward(dom, rms, rows, h):
     rng = np.random.default_rng(rows + h + rms)
     eps = 1e-5
@@ -224,7 +224,7 @@ def _attn_inputs(rng, b, s, nh, d):
 
 
 @pytest.mark.parametrize("d", [64, 80, 128])
-@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3), (1, 64, 1)])
+@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3), (1, 64, 1), (1, 1, 1), (3, 9, 2)])   # s = 1: softmax over one key
 def test_attention_forward(dom, d, b, s, nh):
     rng = np.random.default_rng(d + s)
     hl = nh * d
@@ -243,7 +243,7 @@ def test_attention_forward(dom, d, b, s, nh):
 
 
 @pytest.mark.parametrize("d", [64, 80, 128])
-@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3)])
+@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3), (1, 1, 1), (3, 9, 2)])
 def test_attention_backward(dom, d, b, s, nh):
     rng = np.random.default_rng(d + s + 1)
     hl = nh * d
