@@ -191,77 +191,92 @@ void gemm_kernel(const GemmArgs p) {
 #pragma unroll
   for (int i = 0; i < TN; ++i) asm volatile("" : "+v"(fb[0][i]));
 
-  // ---- epilogue: accumulator (i, j) value v is C[m][n] with
-  //      m = m0 + wm0 + 32 j + lane%32,  n = n0 + wn0 + 32 i + 8 (v/4) + 4 (lane/32) + v%4
+  // ---- epilogue.  Accumulator (i, j) value v of a lane is C[m][n] with
+  //      m = m0 + wm0 + 32 j + lane%32,  n = n0 + wn0 + 32 i + 8 (v/4) + 4 (lane/32) + v%4,
+  // i.e. a lane owns one row: stored from there, every instruction would touch 32 rows with 16 bytes
+  // each.  Each wave therefore turns its 32 x WN blocks through its own piece of the (now free) LDS:
+  // written by row owner, read back with WN/4 consecutive lanes along a row, so that loads of the side
+  // tensors and all stores cover whole 128-byte lines.
+  __builtin_amdgcn_s_barrier();                  // every wave has finished reading the operand stages
+  constexpr int ROWB = WN * 4 + 16;              // padded row: the 16 rows of a write phase hit distinct banks
+  constexpr int LPR = WN / 4;                    // lanes per row when reading back
+  constexpr int RPI = 64 / LPR;                  // rows per read instruction
+  uint8_t* wbuf = smem + wave * (32 * ROWB);
+  const int rrow = lane / LPR, rcol = (lane % LPR) * 4;
   const bool tanh_form = p.gelu_tanh != 0;
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
-    const int m = m0 + wm0 + j * 32 + fr;
-    if (m >= p.M) continue;
 #pragma unroll
-    for (int i = 0; i < TN; ++i) {
+    for (int i = 0; i < TN; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int nl = wn0 + i * 32 + g * 8 + fh * 4;   // tile-local column of the first of 4
-        f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        if constexpr (EPI == EPI_SWIGLU) {
-          if (i & 1) continue;                          // handled together with its gate group
-          const int col = tn * (BN / 2) + ((nl >> 6) << 5) + (nl & 31);
-          if (col >= p.n_split) continue;
-          f32x4 u = {acc[i + 1][j][4 * g], acc[i + 1][j][4 * g + 1], acc[i + 1][j][4 * g + 2], acc[i + 1][j][4 * g + 3]};
-          bf16_t* aux = static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux;
-          u32x2 pg = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-          u32x2 pu = {pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
-          *reinterpret_cast<u32x2*>(aux + col) = pg;
-          *reinterpret_cast<u32x2*>(aux + p.n_split + col) = pu;
-          f32x4 o;
+        const f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        *reinterpret_cast<f32x4*>(wbuf + fr * ROWB + (i * 32 + g * 8 + fh * 4) * 4) = v;
+      }
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = v[e] * sigmoid_f(v[e]) * u[e];
-          u32x2 po = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
-          *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + col) = po;
-        } else {
-          const int n = n0 + nl;
-          if (n >= p.N) continue;
-          if constexpr (EPI == EPI_ACC_F32) {
-            float* c = static_cast<float*>(p.C) + (long)m * p.ldc + n;
-            if (p.beta) {
-              f32x4 old = *reinterpret_cast<const f32x4*>(c);
-              v += old;
-            }
-            *reinterpret_cast<f32x4*>(c) = v;
-          } else {
-            if (p.bias) {
-              const u32x2 bb = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.bias) + n);
-              v[0] += bf16_lo(bb[0]); v[1] += bf16_hi(bb[0]); v[2] += bf16_lo(bb[1]); v[3] += bf16_hi(bb[1]);
-            }
-            if constexpr (EPI == EPI_BIAS_GELU) {
-              u32x2 pp = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux + n) = pp;
+    for (int t = 0; t < 32 / RPI; ++t) {
+      const int row = t * RPI + rrow;
+      const int m = m0 + wm0 + j * 32 + row;
+      const int nl = wn0 + rcol;                 // tile-local column of the first of this lane's 4
+      f32x4 v = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + rcol * 4);
+      if (m >= p.M) continue;
+      if constexpr (EPI == EPI_SWIGLU) {
+        if ((nl >> 5) & 1) continue;             // an up group: handled by the lane holding its gate group
+        const int col = tn * (BN / 2) + ((nl >> 6) << 5) + (nl & 31);
+        if (col >= p.n_split) continue;
+        const f32x4 u = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + (rcol + 32) * 4);
+        bf16_t* aux = static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux;
+        u32x2 pg = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        u32x2 pu = {pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
+        *reinterpret_cast<u32x2*>(aux + col) = pg;
+        *reinterpret_cast<u32x2*>(aux + p.n_split + col) = pu;
+        f32x4 o;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e], tanh_form);
-            } else if constexpr (EPI == EPI_DGELU) {
-              const u32x2 pp = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux + n);
-              v[0] *= gelu_grad_f(bf16_lo(pp[0]), tanh_form); v[1] *= gelu_grad_f(bf16_hi(pp[0]), tanh_form);
-              v[2] *= gelu_grad_f(bf16_lo(pp[1]), tanh_form); v[3] *= gelu_grad_f(bf16_hi(pp[1]), tanh_form);
-            } else if constexpr (EPI == EPI_DSWIGLU) {
-              const bf16_t* aux = static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux;
-              const u32x2 pg = *reinterpret_cast<const u32x2*>(aux + n);
-              const u32x2 pu = *reinterpret_cast<const u32x2*>(aux + p.n_split + n);
-              const float gv[4] = {bf16_lo(pg[0]), bf16_hi(pg[0]), bf16_lo(pg[1]), bf16_hi(pg[1])};
-              const float uv[4] = {bf16_lo(pu[0]), bf16_hi(pu[0]), bf16_lo(pu[1]), bf16_hi(pu[1])};
-              f32x4 du;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const float sg = sigmoid_f(gv[e]);
-                du[e] = v[e] * gv[e] * sg;                                   // d_act * silu(g)
-                v[e] = v[e] * uv[e] * sg * (1.0f + gv[e] * (1.0f - sg));     // d_act * u * silu'(g)
-              }
-              u32x2 pdu = {pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
-              *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + p.n_split + n) = pdu;
-            }
-            u32x2 po = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + n) = po;
+        for (int e = 0; e < 4; ++e) o[e] = v[e] * sigmoid_f(v[e]) * u[e];
+        u32x2 po = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+        *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + col) = po;
+      } else {
+        const int n = n0 + nl;
+        if (n >= p.N) continue;
+        if constexpr (EPI == EPI_ACC_F32) {
+          float* c = static_cast<float*>(p.C) + (long)m * p.ldc + n;
+          if (p.beta) {
+            f32x4 old = *reinterpret_cast<const f32x4*>(c);
+            v += old;
           }
+          *reinterpret_cast<f32x4*>(c) = v;
+        } else {
+          if (p.bias) {
+            const u32x2 bb = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.bias) + n);
+            v[0] += bf16_lo(bb[0]); v[1] += bf16_hi(bb[0]); v[2] += bf16_lo(bb[1]); v[3] += bf16_hi(bb[1]);
+          }
+          if constexpr (EPI == EPI_BIAS_GELU) {
+            u32x2 pp = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux + n) = pp;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e], tanh_form);
+          } else if constexpr (EPI == EPI_DGELU) {
+            const u32x2 pp = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux + n);
+            v[0] *= gelu_grad_f(bf16_lo(pp[0]), tanh_form); v[1] *= gelu_grad_f(bf16_hi(pp[0]), tanh_form);
+            v[2] *= gelu_grad_f(bf16_lo(pp[1]), tanh_form); v[3] *= gelu_grad_f(bf16_hi(pp[1]), tanh_form);
+          } else if constexpr (EPI == EPI_DSWIGLU) {
+            const bf16_t* aux = static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux;
+            const u32x2 pg = *reinterpret_cast<const u32x2*>(aux + n);
+            const u32x2 pu = *reinterpret_cast<const u32x2*>(aux + p.n_split + n);
+            const float gv[4] = {bf16_lo(pg[0]), bf16_hi(pg[0]), bf16_lo(pg[1]), bf16_hi(pg[1])};
+            const float uv[4] = {bf16_lo(pu[0]), bf16_hi(pu[0]), bf16_lo(pu[1]), bf16_hi(pu[1])};
+            f32x4 du;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float sg = sigmoid_f(gv[e]);
+              du[e] = v[e] * gv[e] * sg;                                   // d_act * silu(g)
+              v[e] = v[e] * uv[e] * sg * (1.0f + gv[e] * (1.0f - sg));     // d_act * u * silu'(g)
+            }
+            u32x2 pdu = {pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
+            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + p.n_split + n) = pdu;
+          }
+          u32x2 po = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+          *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + n) = po;
         }
       }
     }
