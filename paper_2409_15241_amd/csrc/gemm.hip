@@ -204,6 +204,28 @@ void gemm_kernel(const GemmArgs p) {
   uint8_t* wbuf = smem + wave * (32 * ROWB);
   const int rrow = lane / LPR, rcol = (lane % LPR) * 4;
   const bool tanh_form = p.gelu_tanh != 0;
+  constexpr int NT_ROWS = 32 / RPI;              // read-back instructions per 32-row block
+
+  // what depends on the lane's 4 columns only
+  const int nl = wn0 + rcol;                     // tile-local column of the first of this lane's 4
+  int n, col = 0;                                // global column; SwiGLU: ffn column of the gate / up pair
+  bool n_ok;
+  if constexpr (EPI == EPI_SWIGLU) {
+    col = tn * (BN / 2) + ((nl >> 6) << 5) + (nl & 31);
+    n = col;
+    n_ok = !((nl >> 5) & 1) && col < p.n_split;  // up groups are handled by the lane holding their gate group
+  } else {
+    n = n0 + nl;
+    n_ok = n < p.N;
+  }
+  f32x4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};
+  if constexpr (EPI == EPI_STORE || EPI == EPI_BIAS_GELU) {
+    if (p.bias && n_ok) {
+      const u32x2 bb = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.bias) + n);
+      bias4 = f32x4{bf16_lo(bb[0]), bf16_hi(bb[0]), bf16_lo(bb[1]), bf16_hi(bb[1])};
+    }
+  }
+
 #pragma unroll
   for (int j = 0; j < TM; ++j) {
 #pragma unroll
@@ -213,71 +235,76 @@ void gemm_kernel(const GemmArgs p) {
         const f32x4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
         *reinterpret_cast<f32x4*>(wbuf + fr * ROWB + (i * 32 + g * 8 + fh * 4) * 4) = v;
       }
+    // phase 1: every load of the block (LDS read-back and side tensors) is issued before any is used; rows or
+    // columns outside the matrix read a safe address instead of branching, their results are never stored
+    f32x4 v[NT_ROWS], u[EPI == EPI_SWIGLU ? NT_ROWS : 1], old[EPI == EPI_ACC_F32 ? NT_ROWS : 1];
+    u32x2 sa[(EPI == EPI_DGELU || EPI == EPI_DSWIGLU) ? NT_ROWS : 1], sb[EPI == EPI_DSWIGLU ? NT_ROWS : 1];
+    bool ok[NT_ROWS];
+    long mrow[NT_ROWS];
 #pragma unroll
-    for (int t = 0; t < 32 / RPI; ++t) {
+    for (int t = 0; t < NT_ROWS; ++t) {
       const int row = t * RPI + rrow;
       const int m = m0 + wm0 + j * 32 + row;
-      const int nl = wn0 + rcol;                 // tile-local column of the first of this lane's 4
-      f32x4 v = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + rcol * 4);
-      if (m >= p.M) continue;
+      ok[t] = n_ok && m < p.M;
+      mrow[t] = ok[t] ? (long)m : 0L;
+      v[t] = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + rcol * 4);
+      if constexpr (EPI == EPI_SWIGLU) u[t] = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + ((rcol + 32) % WN) * 4);
+      const int ns = ok[t] ? n : 0;
+      if constexpr (EPI == EPI_ACC_F32) {
+        if (p.beta) old[t] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p.C) + mrow[t] * p.ldc + ns);
+      } else if constexpr (EPI == EPI_DGELU) {
+        sa[t] = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.aux) + mrow[t] * p.ldaux + ns);
+      } else if constexpr (EPI == EPI_DSWIGLU) {
+        const bf16_t* aux = static_cast<const bf16_t*>(p.aux) + mrow[t] * p.ldaux;
+        sa[t] = *reinterpret_cast<const u32x2*>(aux + ns);
+        sb[t] = *reinterpret_cast<const u32x2*>(aux + p.n_split + ns);
+      }
+    }
+    // phase 2: arithmetic and stores
+#pragma unroll
+    for (int t = 0; t < NT_ROWS; ++t) {
+      f32x4 w = v[t];
       if constexpr (EPI == EPI_SWIGLU) {
-        if ((nl >> 5) & 1) continue;             // an up group: handled by the lane holding its gate group
-        const int col = tn * (BN / 2) + ((nl >> 6) << 5) + (nl & 31);
-        if (col >= p.n_split) continue;
-        const f32x4 u = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + (rcol + 32) * 4);
-        bf16_t* aux = static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux;
-        u32x2 pg = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-        u32x2 pu = {pack_bf16(u[0], u[1]), pack_bf16(u[2], u[3])};
-        *reinterpret_cast<u32x2*>(aux + col) = pg;
-        *reinterpret_cast<u32x2*>(aux + p.n_split + col) = pu;
-        f32x4 o;
+        if (ok[t]) {
+          bf16_t* aux = static_cast<bf16_t*>(p.aux) + mrow[t] * p.ldaux;
+          const u32x2 pg = {pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3])};
+          const u32x2 pu = {pack_bf16(u[t][0], u[t][1]), pack_bf16(u[t][2], u[t][3])};
+          *reinterpret_cast<u32x2*>(aux + col) = pg;
+          *reinterpret_cast<u32x2*>(aux + p.n_split + col) = pu;
+          f32x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = v[e] * sigmoid_f(v[e]) * u[e];
-        u32x2 po = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
-        *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + col) = po;
-      } else {
-        const int n = n0 + nl;
-        if (n >= p.N) continue;
-        if constexpr (EPI == EPI_ACC_F32) {
-          float* c = static_cast<float*>(p.C) + (long)m * p.ldc + n;
-          if (p.beta) {
-            f32x4 old = *reinterpret_cast<const f32x4*>(c);
-            v += old;
-          }
-          *reinterpret_cast<f32x4*>(c) = v;
-        } else {
-          if (p.bias) {
-            const u32x2 bb = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.bias) + n);
-            v[0] += bf16_lo(bb[0]); v[1] += bf16_hi(bb[0]); v[2] += bf16_lo(bb[1]); v[3] += bf16_hi(bb[1]);
-          }
-          if constexpr (EPI == EPI_BIAS_GELU) {
-            u32x2 pp = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.aux) + (long)m * p.ldaux + n) = pp;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e], tanh_form);
-          } else if constexpr (EPI == EPI_DGELU) {
-            const u32x2 pp = *reinterpret_cast<const u32x2*>(static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux + n);
-            v[0] *= gelu_grad_f(bf16_lo(pp[0]), tanh_form); v[1] *= gelu_grad_f(bf16_hi(pp[0]), tanh_form);
-            v[2] *= gelu_grad_f(bf16_lo(pp[1]), tanh_form); v[3] *= gelu_grad_f(bf16_hi(pp[1]), tanh_form);
-          } else if constexpr (EPI == EPI_DSWIGLU) {
-            const bf16_t* aux = static_cast<const bf16_t*>(p.aux) + (long)m * p.ldaux;
-            const u32x2 pg = *reinterpret_cast<const u32x2*>(aux + n);
-            const u32x2 pu = *reinterpret_cast<const u32x2*>(aux + p.n_split + n);
-            const float gv[4] = {bf16_lo(pg[0]), bf16_hi(pg[0]), bf16_lo(pg[1]), bf16_hi(pg[1])};
-            const float uv[4] = {bf16_lo(pu[0]), bf16_hi(pu[0]), bf16_lo(pu[1]), bf16_hi(pu[1])};
-            f32x4 du;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float sg = sigmoid_f(gv[e]);
-              du[e] = v[e] * gv[e] * sg;                                   // d_act * silu(g)
-              v[e] = v[e] * uv[e] * sg * (1.0f + gv[e] * (1.0f - sg));     // d_act * u * silu'(g)
-            }
-            u32x2 pdu = {pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
-            *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + p.n_split + n) = pdu;
-          }
-          u32x2 po = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-          *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + (long)m * p.ldc + n) = po;
+          for (int e = 0; e < 4; ++e) o[e] = w[e] * sigmoid_f(w[e]) * u[t][e];
+          const u32x2 po = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+          *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + mrow[t] * p.ldc + col) = po;
         }
+      } else if constexpr (EPI == EPI_ACC_F32) {
+        if (p.beta) w += old[t];
+        if (ok[t]) *reinterpret_cast<f32x4*>(static_cast<float*>(p.C) + mrow[t] * p.ldc + n) = w;
+      } else {
+        w += bias4;
+        if constexpr (EPI == EPI_BIAS_GELU) {
+          const u32x2 pp = {pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3])};
+          if (ok[t]) *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.aux) + mrow[t] * p.ldaux + n) = pp;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = gelu_f(w[e], tanh_form);
+        } else if constexpr (EPI == EPI_DGELU) {
+          w[0] *= gelu_grad_f(bf16_lo(sa[t][0]), tanh_form); w[1] *= gelu_grad_f(bf16_hi(sa[t][0]), tanh_form);
+          w[2] *= gelu_grad_f(bf16_lo(sa[t][1]), tanh_form); w[3] *= gelu_grad_f(bf16_hi(sa[t][1]), tanh_form);
+        } else if constexpr (EPI == EPI_DSWIGLU) {
+          const float gv[4] = {bf16_lo(sa[t][0]), bf16_hi(sa[t][0]), bf16_lo(sa[t][1]), bf16_hi(sa[t][1])};
+          const float uv[4] = {bf16_lo(sb[t][0]), bf16_hi(sb[t][0]), bf16_lo(sb[t][1]), bf16_hi(sb[t][1])};
+          f32x4 du;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float sg = sigmoid_f(gv[e]);
+            du[e] = w[e] * gv[e] * sg;                                   // d_act * silu(g)
+            w[e] = w[e] * uv[e] * sg * (1.0f + gv[e] * (1.0f - sg));     // d_act * u * silu'(g)
+          }
+          const u32x2 pdu = {pack_bf16(du[0], du[1]), pack_bf16(du[2], du[3])};
+          if (ok[t]) *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + mrow[t] * p.ldc + p.n_split + n) = pdu;
+        }
+        const u32x2 po = {pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3])};
+        if (ok[t]) *reinterpret_cast<u32x2*>(static_cast<bf16_t*>(p.C) + mrow[t] * p.ldc + n) = po;
       }
     }
   }
