@@ -21,6 +21,8 @@ DEV u32x4 pack8(const float* f) {
 
 // y = Norm(x + add1 + add2 + vec) * gamma + beta; optionally writes the pre-norm sum (bf16) too.
 // The statistics are taken from the bf16-rounded sum, i.e. from exactly what the backward re-reads.
+// Every load of a phase is issued before the first is used (chunks past the row end read the last chunk
+// instead of branching, and are masked out of the sums and stores): a wave has 10-40 loads in flight.
 template <int NC, bool RMS>
 __global__ __launch_bounds__(256)
 void norm_fwd_kernel(const NormFwdArgs p) {
@@ -35,40 +37,57 @@ void norm_fwd_kernel(const NormFwdArgs p) {
   const u32x4* vec = reinterpret_cast<const u32x4*>(p.vec);
   const bool fused = a1 || a2 || vec;
 
-  u32x4 xs[NC];
+  int cc[NC];                                   // chunk index, clamped into the row
+  bool live[NC];
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
     const int c = lane + 64 * i;
-    u32x4 z = {0u, 0u, 0u, 0u};
-    xs[i] = c < nch ? x[c] : z;
+    live[i] = c < nch;
+    cc[i] = live[i] ? c : nch - 1;
   }
+  u32x4 xs[NC];
+#pragma unroll
+  for (int i = 0; i < NC; ++i) xs[i] = x[cc[i]];
   if (fused) {
+    u32x4 t1[NC], t2[NC], t3[NC];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < NC; ++i) t1[i] = a1 ? a1[cc[i]] : zero4;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) t2[i] = a2 ? a2[cc[i]] : zero4;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) t3[i] = vec ? vec[cc[i]] : zero4;
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
-      const int c = lane + 64 * i;
-      if (c < nch) {
-        float f[8], g[8];
-        unpack8(xs[i], f);
-        if (a1) { unpack8(a1[c], g);
+      float f[8], g[8];
+      unpack8(xs[i], f);
+      unpack8(t1[i], g);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] += g[e]; }
-        if (a2) { unpack8(a2[c], g);
+      for (int e = 0; e < 8; ++e) f[e] += g[e];
+      unpack8(t2[i], g);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] += g[e]; }
-        if (vec) { unpack8(vec[c], g);
+      for (int e = 0; e < 8; ++e) f[e] += g[e];
+      unpack8(t3[i], g);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] += g[e]; }
-        xs[i] = pack8(f);
-      }
+      for (int e = 0; e < 8; ++e) f[e] += g[e];
+      xs[i] = pack8(f);
     }
     if (p.xsum) {
       u32x4* o = reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.xsum) + ro);
 #pragma unroll
-      for (int i = 0; i < NC; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nch) o[c] = xs[i];
-      }
+      for (int i = 0; i < NC; ++i)
+        if (live[i]) o[cc[i]] = xs[i];
     }
+  }
+  // gain and shift for the last phase: in flight during the reductions
+  const u32x4* gam = reinterpret_cast<const u32x4*>(p.gamma);
+  const u32x4* bet = reinterpret_cast<const u32x4*>(p.beta);
+  u32x4 gs[NC], bs[NC];
+#pragma unroll
+  for (int i = 0; i < NC; ++i) gs[i] = gam[cc[i]];
+  if (bet) {
+#pragma unroll
+    for (int i = 0; i < NC; ++i) bs[i] = bet[cc[i]];
   }
 
   const float inv_h = 1.0f / (float)p.h;
@@ -78,45 +97,41 @@ void norm_fwd_kernel(const NormFwdArgs p) {
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
       float f[8]; unpack8(xs[i], f);
+      float t = 0.0f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s += f[e];
+      for (int e = 0; e < 8; ++e) t += f[e];
+      s += live[i] ? t : 0.0f;
     }
     mean = wave_sum(s) * inv_h;
   }
   float ss = 0.0f;
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
-    const int c = lane + 64 * i;
-    if (c < nch) {
-      float f[8]; unpack8(xs[i], f);
+    float f[8]; unpack8(xs[i], f);
+    float t = 0.0f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; ss += d * d; }
-    }
+    for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; t += d * d; }
+    ss += live[i] ? t : 0.0f;
   }
   const float rstd = rsqrtf(wave_sum(ss) * inv_h + p.eps);
   if (lane == 0) {
     if (p.mean) p.mean[row] = mean;
     p.rstd[row] = rstd;
   }
-  const u32x4* gam = reinterpret_cast<const u32x4*>(p.gamma);
-  const u32x4* bet = reinterpret_cast<const u32x4*>(p.beta);
   u32x4* y = reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.y) + ro);
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
-    const int c = lane + 64 * i;
-    if (c < nch) {
-      float f[8], g[8];
-      unpack8(xs[i], f);
-      unpack8(gam[c], g);
+    float f[8], g[8];
+    unpack8(xs[i], f);
+    unpack8(gs[i], g);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = (f[e] - mean) * rstd * g[e];
-      if (bet) {
-        unpack8(bet[c], g);
+    for (int e = 0; e < 8; ++e) f[e] = (f[e] - mean) * rstd * g[e];
+    if (bet) {
+      unpack8(bs[i], g);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] += g[e];
-      }
-      y[c] = pack8(f);
+      for (int e = 0; e < 8; ++e) f[e] += g[e];
     }
+    if (live[i]) y[cc[i]] = pack8(f);
   }
 }
 
