@@ -33,20 +33,18 @@ void residual_out_kernel(const u32x4* __restrict__ x1, const u32x4* __restrict__
                          const u32x4* __restrict__ vec, u32x4* __restrict__ y, long nchunks, int hch) {
   const long c = (long)blockIdx.x * 256 + threadIdx.x;
   if (c >= nchunks) return;
+  // all four loads are issued before the first use: absent operands read x1 again and are dropped
   const u32x4 vx = x1[c], va = a[c];
+  const u32x4 vb = (b ? b : x1)[c];
+  const u32x4 vv = (vec ? vec : x1)[vec ? c % hch : c];
   float f[8] = {bf16_lo(vx[0]) + bf16_lo(va[0]), bf16_hi(vx[0]) + bf16_hi(va[0]),
                 bf16_lo(vx[1]) + bf16_lo(va[1]), bf16_hi(vx[1]) + bf16_hi(va[1]),
                 bf16_lo(vx[2]) + bf16_lo(va[2]), bf16_hi(vx[2]) + bf16_hi(va[2]),
                 bf16_lo(vx[3]) + bf16_lo(va[3]), bf16_hi(vx[3]) + bf16_hi(va[3])};
-  if (b) {
-    const u32x4 v = b[c];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { f[2 * e] += bf16_lo(v[e]); f[2 * e + 1] += bf16_hi(v[e]); }
-  }
-  if (vec) {
-    const u32x4 v = vec[c % hch];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { f[2 * e] += bf16_lo(v[e]); f[2 * e + 1] += bf16_hi(v[e]); }
+  for (int e = 0; e < 4; ++e) {
+    f[2 * e] += (b ? bf16_lo(vb[e]) : 0.0f) + (vec ? bf16_lo(vv[e]) : 0.0f);
+    f[2 * e + 1] += (b ? bf16_hi(vb[e]) : 0.0f) + (vec ? bf16_hi(vv[e]) : 0.0f);
   }
   u32x4 o = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
   y[c] = o;
