@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--layers", type=int, default=1,
+                    help="blocks per step: above 1 the step is domino_stack_fwd + domino_stack_bwd over that many "
+                         "blocks (row slices run on from block to block without joining)")
     ap.add_argument("--graph", action="store_true", help="capture the step in a HIP graph and replay it")
     ap.add_argument("--p", type=int, default=None)
     ap.add_argument("--q", type=int, default=None)
@@ -132,7 +135,11 @@ def main():
     params = synth.make_rank_params(sc)
     x, dy = synth.make_activations(sc)
     others = synth.make_others(sc)
-    buf = harness.LayerBuffers(sc, params, x, dy, others, nstreams=args.streams)
+    if args.layers > 1:
+        params_l, others_l = synth.make_stack(sc, args.layers)
+        buf = harness.StackBuffers(sc, params_l, x, dy, others_l, nstreams=args.streams)
+    else:
+        buf = harness.LayerBuffers(sc, params, x, dy, others, nstreams=args.streams)
     s0 = buf.streams[0]
 
     def eager_step():
@@ -163,7 +170,7 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms = wall * 1e3 / args.steps
-    flops = algorithmic_flops(sc)
+    flops = algorithmic_flops(sc) * args.layers
     value = flops / (ms * 1e-3) / 1e12
 
     # forward-only / backward-only, event-timed on streams[0] (where the library joins its streams)
@@ -264,7 +271,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": sc.name, "hidden": sc.hidden, "heads": sc.heads, "tp": sc.tp, "rank": sc.rank,
                    "batch": sc.batch, "seq": sc.seq, "ffn": sc.ffn, "p": sc.p, "q": sc.q,
-                   "arch": "llama" if sc.arch else "gpt", "streams": args.streams},
+                   "arch": "llama" if sc.arch else "gpt", "streams": args.streams, "layers": args.layers},
         "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "algorithmic_gflop_per_step": flops / 1e9, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "roofline": roofline, "cpu_baseline": cpu,

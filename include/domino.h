@@ -115,6 +115,48 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* params, const v
                      void* workspace, size_t workspace_bytes,
                      void* const* streams, int nstreams);
 
+/* ---- a stack of blocks (Sec. 2.3: N blocks one after the other; Sec. 3.2 and 4.1.1: the row slices stay
+ * independent from block to block, so slice 0 of block l+1 starts while the other slices of block l still run) --- */
+
+/* Buffers of one block of a stack in the forward: meanings as in domino_layer_fwd.  y is required (it is the
+ * next block's input; the last block's y is the stack's output). */
+typedef struct domino_stack_fwd_io {
+  const void *attn_others, *mlp_others;     /* [b,s,h] or NULL */
+  void *attn_partial, *mlp_partial, *y;     /* out [b,s,h] */
+  void *saved;                              /* out, domino_saved_bytes() */
+} domino_stack_fwd_io;
+
+/* Buffers of one block of a stack in the backward: meanings as in domino_layer_bwd.  x is the block's forward
+ * input (the stack's x for block 0, block l-1's y otherwise), saved the block's saved activations. */
+typedef struct domino_stack_bwd_io {
+  const void *x, *saved;
+  const void *dln2_others, *dln1_others;    /* [b,s,h] or NULL */
+  void *dln2_partial, *dln1_partial;        /* out [b,s,h] */
+} domino_stack_bwd_io;
+
+/* Workspace bytes of a stack of nlayers blocks (1..1024): one block's workspace, one area of partial
+ * vector-gradient sums per further block, and the [b,s,h] gradient handed from block to block.  0 on error. */
+size_t domino_stack_workspace_bytes(const domino_cfg* cfg, int nlayers);
+
+/* Forward of nlayers blocks of the same configuration, params[l] and io[l] being block l's (host arrays of
+ * nlayers structs).  Row slice i of every block runs on the stream domino_layer_fwd would give it, and the
+ * only joins are the column synchronisations inside a block and one join onto streams[0] after the last
+ * block: no stream waits for another between blocks.  Results are bitwise those of nlayers calls of
+ * domino_layer_fwd with y of one as x of the next. */
+int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* x,
+                     const domino_stack_fwd_io* io, void* workspace, size_t workspace_bytes,
+                     void* const* streams, int nstreams);
+
+/* Backward of the stack for L = sum(y_last * dy): blocks nlayers-1 .. 0, dx of one being dy of the one below
+ * (kept in the workspace).  grads[l] are block l's gradients (host array of nlayers structs); accumulate as
+ * in domino_layer_bwd.  Within a block the weight gradients are still summed in slice order; between blocks a
+ * slice goes on without waiting for the others, and each block's vector gradients are reduced on the last
+ * slice's stream once all slices have left the block.  Results are bitwise those of nlayers calls of
+ * domino_layer_bwd. */
+int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* dy,
+                     const domino_stack_bwd_io* io, void* dx, const domino_grads* grads, int accumulate,
+                     void* workspace, size_t workspace_bytes, void* const* streams, int nstreams);
+
 /* ---- single kernels (the steps above, exposed for unit parity tests and roofline runs) ---------- */
 
 enum { DOMINO_GEMM_NN = 0,   /* C[M,N] = A[M,K] * B[K,N]        forward products (Eq. 1-4)            */

@@ -581,6 +581,36 @@ def simulate_tp(cfg, shards, x, dy):
     return fwd, bwd
 
 
+# --------------------------------------------------------------------------- a stack of blocks
+def rank_stack_fwd(cfg, Ps, x, others=None):
+    """N blocks one after the other (Sec. 2.3): block l's input is block l-1's output y.
+
+    Ps is a list of parameter dicts; ``others`` an optional list of dicts with attn_others /
+    mlp_others per block.  Returns the list of per-block forward dicts (the last one's 'y' is
+    the stack's output)."""
+    outs = []
+    cur = _f(x)
+    for l, P in enumerate(Ps):
+        o = {} if others is None else others[l]
+        S = rank_layer_fwd(cfg, P, cur, o.get("attn_others"), o.get("mlp_others"))
+        outs.append(S)
+        cur = S["y"]
+    return outs
+
+
+def rank_stack_bwd(cfg, Ps, Ss, dy, others=None):
+    """Backward of rank_stack_fwd for L = sum(y_last * dy): the blocks in reverse, dx of block l
+    being dy of block l-1.  Returns the list of per-block backward dicts in block order (the
+    first one's 'dx' is the gradient of the stack's input)."""
+    outs = [None] * len(Ps)
+    cur = _f(dy)
+    for l in reversed(range(len(Ps))):
+        o = {} if others is None else others[l]
+        outs[l] = rank_layer_bwd(cfg, Ps[l], Ss[l], cur, o.get("dln2_others"), o.get("dln1_others"))
+        cur = outs[l]["dx"]
+    return outs
+
+
 # --------------------------------------------------------------------------- flop bookkeeping
 def algorithmic_flops(cfg):
     """Forward+backward matmul flops of one rank's layer: causal attention counted at half the

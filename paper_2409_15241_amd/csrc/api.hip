@@ -239,6 +239,325 @@ int check_params(const Layout& L, const domino_params* P) {
   return DOMINO_OK;
 }
 
+
+// ---------------------------------------------------------------------------------- the piece schedule
+// One block's buffers as the forward / the backward sees them (all device pointers, caller-owned).
+struct FwdLayer {
+  const domino_params* P;
+  const void *x, *attn_others, *mlp_others;
+  void *attn_partial, *mlp_partial, *y, *saved;
+};
+struct BwdLayer {
+  const domino_params* P;
+  const domino_grads* G;
+  const void *saved, *x, *dy, *dln2_others, *dln1_others;
+  void *dln2_partial, *dln1_partial, *dx;
+  float* red;        // this block's partial column sums: p slices of red_floats floats
+  int accumulate;
+};
+
+// which stream of the pool carries which piece (Sec. 4.3.1: a fixed pool, picked by index)
+struct StreamPlan {
+  void* const* streams;
+  int ns, p, q, nslice;
+  bool wide;                                                // enough streams for every column piece
+  StreamPlan(void* const* s, int n, int p_, int q_)
+      : streams(s), ns(n), p(p_), q(q_), nslice(p_ < n ? p_ : n), wide(n >= p_ * q_) {}
+  int piece_index(int i, int j) const { return (wide && j > 0) ? i + j * p : i % nslice; }
+  hipStream_t slice(int i) const { return as_stream(streams[i % nslice]); }
+  hipStream_t piece(int i, int j) const { return as_stream(streams[piece_index(i, j)]); }
+  // streams that a forward call touches; the backward touches the first nslice only
+  std::vector<char> used_fwd() const {
+    std::vector<char> u(ns, 0);
+    for (int i = 0; i < p; ++i)
+      for (int j = 0; j < q; ++j) u[piece_index(i, j)] = 1;
+    return u;
+  }
+};
+
+// fork: one event on streams[0]; every other stream marked in `used` waits for it
+int fork_streams(const StreamPlan& S, const std::vector<char>& used) {
+  hipEvent_t fork;
+  TRY(next_sync_event(&fork));
+  HIP_TRY(hipEventRecord(fork, as_stream(S.streams[0])), "hipEventRecord");
+  for (int k = 1; k < S.ns; ++k)
+    if (used[k]) HIP_TRY(hipStreamWaitEvent(as_stream(S.streams[k]), fork, 0), "hipStreamWaitEvent");
+  return DOMINO_OK;
+}
+int join_streams(const StreamPlan& S, const std::vector<char>& used) {
+  for (int k = 1; k < S.ns; ++k)
+    if (used[k]) TRY(edge(as_stream(S.streams[k]), as_stream(S.streams[0])));
+  return DOMINO_OK;
+}
+
+int check_fwd_layer(const Layout& L, const FwdLayer& B) {
+  TRY(check_params(L, B.P));
+  if (!B.x || !B.attn_partial || !B.mlp_partial || !B.saved) return fail(DOMINO_ERR_NULL_POINTER, "x, attn_partial, mlp_partial or saved is NULL");
+  return DOMINO_OK;
+}
+
+int check_bwd_layer(const Layout& L, const BwdLayer& B) {
+  TRY(check_params(L, B.P));
+  const domino_grads* G = B.G;
+  if (!B.saved || !B.x || !B.dy || !B.dln2_partial || !B.dln1_partial || !B.dx || !G)
+    return fail(DOMINO_ERR_NULL_POINTER, "saved, x, dy, dln2_partial, dln1_partial, dx or grads is NULL");
+  if (!G->norm1_g || !G->norm2_g || !G->w_qkv || !G->w_o || !G->w_up || !G->w_down)
+    return fail(DOMINO_ERR_NULL_POINTER, "a weight or norm-gain gradient pointer is NULL");
+  if (!L.llama && (!G->norm1_b || !G->norm2_b || !G->b_qkv || !G->b_o || !G->b_up || !G->b_down))
+    return fail(DOMINO_ERR_NULL_POINTER, "a GPT bias or norm-shift gradient pointer is NULL");
+  return DOMINO_OK;
+}
+
+// Forward of row slice i of one block (Sec. 3.2, Eq. 3): every kernel of the slice on its own stream, the q
+// column pieces of the two row-cut products (Sec. 3.3, Eq. 4) written in place into the full-width buffers.
+int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& S, const FwdLayer& B, int i) {
+  const domino_params* P = B.P;
+  const int Ms = L.Ms;
+  const bool rms = L.llama;
+  hipStream_t st = S.slice(i);
+  const size_t r0 = (size_t)i * Ms;                       // first token row of the slice
+  const size_t rh = r0 * L.h * 2;                         // byte offset into [M, h] bf16 tensors
+  const char* xi = at(B.x, rh);
+  void* saved = B.saved;
+  char* ln1 = at(saved, L.ln1 + rh);
+  char* qkv = at(saved, L.qkv + r0 * 3 * L.hl * 2);
+  char* ctx = at(saved, L.ctx + r0 * L.hl * 2);
+  float* lse = reinterpret_cast<float*>(at(saved, L.lse)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
+  char* x1 = at(saved, L.x1 + rh);
+  char* ln2 = at(saved, L.ln2 + rh);
+  char* pre = at(saved, L.pre + r0 * L.upc * 2);
+  char* act = at(saved, L.act + r0 * L.fl * 2);
+  float* mean1 = reinterpret_cast<float*>(at(saved, L.mean1)) + r0;
+  float* rstd1 = reinterpret_cast<float*>(at(saved, L.rstd1)) + r0;
+  float* mean2 = reinterpret_cast<float*>(at(saved, L.mean2)) + r0;
+  float* rstd2 = reinterpret_cast<float*>(at(saved, L.rstd2)) + r0;
+
+  {  // F1: Norm1
+    ProfScope ps(PC_NORM_FWD, st);
+    NormFwdArgs a{};
+    a.x = xi; a.gamma = P->norm1_g; a.beta = P->norm1_b; a.y = ln1; a.mean = rms ? nullptr : mean1; a.rstd = rstd1;
+    a.rows = Ms; a.h = L.h; a.rms = rms; a.eps = cfg->norm_eps;
+    LAUNCH(norm_fwd_launch(a, st), "norm1 forward");
+  }
+  {  // F2: X * A (attention), column-parallel, never column-sliced
+    ProfScope ps(PC_GEMM_QKV, st);
+    GemmArgs a = gemm_args(ln1, L.h, P->w_qkv, 3 * L.hl, qkv, 3 * L.hl, Ms, 3 * L.hl, L.h);
+    a.bias = P->b_qkv;
+    LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "qkv product");
+  }
+  if (L.llama) {
+    ProfScope ps(PC_ROPE, st);
+    LAUNCH(rope_launch(qkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 0, st), "rotary embedding");
+  }
+  {  // F3
+    ProfScope ps(PC_ATTN_FWD, st);
+    AttnArgs a{};
+    a.qkv = qkv; a.ld = 3 * L.hl; a.ctx = ctx; a.ld_ctx = L.hl; a.lse = lse;
+    a.batch = L.b / L.p; a.seq = L.s; a.heads = L.nl; a.head_dim = L.d; a.scale = 1.0f / sqrtf((float)L.d);
+    LAUNCH(attention_fwd_launch(a, st), "attention forward");
+  }
+  // F4: (XA) * B_j, one piece per column slice, written in place into the full-width buffer
+  for (int j = 0; j < L.q; ++j) {
+    hipStream_t sj = S.piece(i, j);
+    TRY(edge(st, sj));
+    {
+      ProfScope ps(PC_GEMM_OUT, sj);
+      const size_t cj = (size_t)j * L.hq * 2;
+      GemmArgs a = gemm_args(ctx, L.hl, at(P->w_o, cj), L.h, at(B.attn_partial, rh + cj), L.h, Ms, L.hq, L.hl);
+      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "out-projection piece");
+    }
+    TRY(edge(sj, st));                                    // column synchronisation before Norm2
+  }
+  {  // F5: residual + reduced attention output + Norm2
+    ProfScope ps(PC_NORM_FWD, st);
+    NormFwdArgs a{};
+    a.x = xi; a.add1 = at(B.attn_partial, rh); a.add2 = B.attn_others ? at(B.attn_others, rh) : nullptr; a.vec = P->b_o;
+    a.gamma = P->norm2_g; a.beta = P->norm2_b; a.xsum = x1; a.y = ln2; a.mean = rms ? nullptr : mean2; a.rstd = rstd2;
+    a.rows = Ms; a.h = L.h; a.rms = rms; a.eps = cfg->norm_eps;
+    LAUNCH(norm_fwd_launch(a, st), "norm2 forward");
+  }
+  {  // F6: X * A (MLP) with the activation fused
+    ProfScope ps(PC_GEMM_UP, st);
+    GemmArgs a = gemm_args(ln2, L.h, P->w_up, L.upc, act, L.fl, Ms, L.fl, L.h);
+    a.aux = pre; a.ldaux = L.upc; a.gelu_tanh = cfg->gelu_tanh;
+    if (L.llama) { a.n_split = L.fl; LAUNCH(gemm_launch(GEMM_NN, EPI_SWIGLU, a, -1, st), "mlp-up product"); }
+    else { a.bias = P->b_up; LAUNCH(gemm_launch(GEMM_NN, EPI_BIAS_GELU, a, -1, st), "mlp-up product"); }
+  }
+  for (int j = 0; j < L.q; ++j) {  // F7
+    hipStream_t sj = S.piece(i, j);
+    TRY(edge(st, sj));
+    {
+      ProfScope ps(PC_GEMM_DOWN, sj);
+      const size_t cj = (size_t)j * L.hq * 2;
+      GemmArgs a = gemm_args(act, L.fl, at(P->w_down, cj), L.h, at(B.mlp_partial, rh + cj), L.h, Ms, L.hq, L.fl);
+      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "mlp-down piece");
+    }
+    TRY(edge(sj, st));
+  }
+  if (B.y) {  // F8
+    ProfScope ps(PC_RESID_OUT, st);
+    LAUNCH(residual_out_launch(x1, at(B.mlp_partial, rh), B.mlp_others ? at(B.mlp_others, rh) : nullptr, P->b_down,
+                               at(B.y, rh), (long)Ms * L.h, L.h, st), "block output");
+  }
+  return DOMINO_OK;
+}
+
+// Weight gradients are summed over the row slices in slice order: slice i's product into a matrix waits for
+// slice i-1's product into the same matrix (one event per matrix).
+struct WgChain {
+  hipStream_t prev = nullptr;
+  hipEvent_t done[4] = {}, cur[4] = {};
+};
+
+// Backward of row slice i of one block; within the slice each input gradient is enqueued before the weight
+// gradient of the same product (Sec. 4.1.2).
+int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStream_t st, const BwdLayer& B, int i,
+                      WgChain& wg) {
+  const domino_params* P = B.P;
+  const domino_grads* G = B.G;
+  const void* saved = B.saved;
+  const int Ms = L.Ms;
+  const bool rms = L.llama;
+  const size_t r0 = (size_t)i * Ms;
+  const size_t rh = r0 * L.h * 2;
+  const char* xi = at(B.x, rh);
+  const char* dyi = at(B.dy, rh);
+  const char* ln1 = at(saved, L.ln1 + rh);
+  const char* qkv = at(saved, L.qkv + r0 * 3 * L.hl * 2);
+  const char* ctx = at(saved, L.ctx + r0 * L.hl * 2);
+  const float* lse = reinterpret_cast<const float*>(at(saved, L.lse)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
+  const char* x1 = at(saved, L.x1 + rh);
+  const char* ln2 = at(saved, L.ln2 + rh);
+  const char* pre = at(saved, L.pre + r0 * L.upc * 2);
+  const char* act = at(saved, L.act + r0 * L.fl * 2);
+  const float* mean1 = reinterpret_cast<const float*>(at(saved, L.mean1)) + r0;
+  const float* rstd1 = reinterpret_cast<const float*>(at(saved, L.rstd1)) + r0;
+  const float* mean2 = reinterpret_cast<const float*>(at(saved, L.mean2)) + r0;
+  const float* rstd2 = reinterpret_cast<const float*>(at(saved, L.rstd2)) + r0;
+  char* d_pre = at(ws, L.d_pre + r0 * L.upc * 2);
+  char* dx1 = at(ws, L.dx1 + rh);
+  char* dctx = at(ws, L.dctx + r0 * L.hl * 2);
+  char* dqkv = at(ws, L.dqkv + r0 * 3 * L.hl * 2);
+  float* dot = reinterpret_cast<float*>(at(ws, L.dot)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
+  float* red = B.red + (size_t)i * L.red_floats;
+  auto area = [&](int k) { return red + L.area_off[k]; };
+  const int beta = (i > 0 || B.accumulate) ? 1 : 0;
+  const bool chain = wg.prev && wg.prev != st;
+
+  auto wgrad = [&](int which, int cls, const void* A, long lda, const void* Bm, long ldb, float* C, long ldc,
+                   int M, int N) -> int {
+    if (chain) HIP_TRY(hipStreamWaitEvent(st, wg.done[which], 0), "hipStreamWaitEvent");
+    {
+      ProfScope ps(cls, st);
+      GemmArgs a = gemm_args(A, lda, Bm, ldb, C, ldc, M, N, Ms);
+      a.beta = beta;
+      LAUNCH(gemm_launch(GEMM_TN, EPI_ACC_F32, a, -1, st), "weight gradient");
+    }
+    TRY(next_sync_event(&wg.cur[which]));
+    HIP_TRY(hipEventRecord(wg.cur[which], st), "hipEventRecord");
+    return DOMINO_OK;
+  };
+  auto colsum = [&](const void* g, long ld, int n, int k) -> int {
+    ProfScope ps(PC_COLSUM, st);
+    LAUNCH(colsum_partial_launch(g, ld, Ms, n, area(k), st), "bias gradient");
+    return DOMINO_OK;
+  };
+  auto norm_bwd = [&](const void* ga, const void* gb, const void* xin, const void* gamma, const float* mean,
+                      const float* rstd, const void* dres, void* out, int kg, int kb, int kres = -1, int kdx = -1) -> int {
+    ProfScope ps(PC_NORM_BWD, st);
+    NormBwdArgs a{};
+    a.ga = ga; a.gb = gb; a.x = xin; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dres = dres; a.dx = out;
+    a.part_g = area(kg); a.part_b = area(kb); a.rows = Ms; a.h = L.h; a.rms = rms;
+    if (kres >= 0) { a.part_dres = area(kres); a.part_dx = area(kdx); }   // bias gradients of the two row-cut products
+    LAUNCH(norm_bwd_launch(a, st), "norm backward");
+    return DOMINO_OK;
+  };
+
+  {  // B1 + B3: input gradient of the down-projection (all q column slices inside the K loop), activation backward fused
+    ProfScope ps(PC_DGRAD_DOWN, st);
+    GemmArgs a = gemm_args(dyi, L.h, P->w_down, L.h, d_pre, L.upc, Ms, L.fl, L.h);
+    a.aux = const_cast<char*>(pre); a.ldaux = L.upc; a.gelu_tanh = cfg->gelu_tanh;
+    if (L.llama) { a.n_split = L.fl; LAUNCH(gemm_launch(GEMM_NT, EPI_DSWIGLU, a, -1, st), "mlp-down input gradient"); }
+    else LAUNCH(gemm_launch(GEMM_NT, EPI_DGELU, a, -1, st), "mlp-down input gradient");
+  }
+  TRY(wgrad(0, PC_WGRAD_DOWN, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
+  {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
+    ProfScope ps(PC_DGRAD_UP, st);
+    GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(B.dln2_partial, rh), L.h, Ms, L.h, L.upc);
+    LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "mlp-up input gradient");
+  }
+  TRY(wgrad(1, PC_WGRAD_UP, ln2, L.h, d_pre, L.upc, G->w_up, L.upc, L.h, L.upc));
+  if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, AREA_BUP));
+  // B5
+  TRY(norm_bwd(at(B.dln2_partial, rh), B.dln2_others ? at(B.dln2_others, rh) : nullptr, x1, P->norm2_g, mean2, rstd2,
+               dyi, dx1, AREA_G2, AREA_B2, L.llama ? -1 : AREA_BDOWN, L.llama ? -1 : AREA_BO));
+  {  // B6
+    ProfScope ps(PC_DGRAD_OUT, st);
+    GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
+    LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "out-projection input gradient");
+  }
+  TRY(wgrad(2, PC_WGRAD_OUT, ctx, L.hl, dx1, L.h, G->w_o, L.h, L.hl, L.h));
+  {  // B7
+    ProfScope ps(PC_ATTN_BWD, st);
+    AttnArgs a{};
+    a.qkv = qkv; a.ld = 3 * L.hl; a.ctx = const_cast<char*>(ctx); a.ld_ctx = L.hl; a.dctx = dctx;
+    a.lse = const_cast<float*>(lse); a.dot = dot; a.dqkv = dqkv;
+    a.batch = L.b / L.p; a.seq = L.s; a.heads = L.nl; a.head_dim = L.d; a.scale = 1.0f / sqrtf((float)L.d);
+    LAUNCH(attention_bwd_launch(a, st), "attention backward");
+  }
+  if (L.llama) {
+    ProfScope ps(PC_ROPE, st);
+    LAUNCH(rope_launch(dqkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 1, st), "rotary embedding backward");
+  }
+  {  // B8: input gradient of QKV: the tensor the fourth all-reduce would sum
+    ProfScope ps(PC_DGRAD_QKV, st);
+    GemmArgs a = gemm_args(dqkv, 3 * L.hl, P->w_qkv, 3 * L.hl, at(B.dln1_partial, rh), L.h, Ms, L.h, 3 * L.hl);
+    LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "qkv input gradient");
+  }
+  TRY(wgrad(3, PC_WGRAD_QKV, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
+  if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, AREA_BQKV));
+  TRY(norm_bwd(at(B.dln1_partial, rh), B.dln1_others ? at(B.dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
+               dx1, at(B.dx, rh), AREA_G1, AREA_B1));
+
+  wg.prev = st;
+  for (int k = 0; k < 4; ++k) wg.done[k] = wg.cur[k];
+  return DOMINO_OK;
+}
+
+// vector gradients of one block: one launch sums, for every vector, the partial rows of all slices in slice order
+int enqueue_vector_grads(const Layout& L, const BwdLayer& B, hipStream_t st) {
+  ProfScope ps(PC_COLSUM, st);
+  const domino_grads* G = B.G;
+  struct { int k; float* out; } vec[NAREAS] = {
+    {AREA_G1, G->norm1_g}, {AREA_B1, G->norm1_b}, {AREA_G2, G->norm2_g}, {AREA_B2, G->norm2_b},
+    {AREA_BQKV, G->b_qkv}, {AREA_BO, G->b_o}, {AREA_BUP, G->b_up}, {AREA_BDOWN, G->b_down}};
+  ColsumJobs jobs{};
+  int njobs = 0;
+  for (auto& v : vec) {
+    if (!v.out) continue;
+    if (L.llama && v.k != AREA_G1 && v.k != AREA_G2) continue;
+    jobs.job[njobs++] = {B.red + L.area_off[v.k], v.out, L.area_rows[v.k], L.area_n[v.k], (long)L.area_n[v.k],
+                         L.p, (long)L.red_floats};
+  }
+  LAUNCH(colsum_finish_jobs_launch(jobs, njobs, B.accumulate, st), "vector gradient reduction");
+  return DOMINO_OK;
+}
+
+// workspace of a stack: one block's workspace, the partial-sum areas of the other blocks, and the gradient
+// tensor handed from block to block
+struct StackLayout {
+  size_t red_bytes, extra_red, dmid, total;
+};
+StackLayout stack_layout(const Layout& L, int nlayers) {
+  StackLayout s{};
+  s.red_bytes = align_up((size_t)L.p * L.red_floats * 4);
+  s.extra_red = L.ws_total;
+  s.dmid = s.extra_red + (size_t)(nlayers - 1) * s.red_bytes;
+  s.total = s.dmid + align_up((size_t)L.M * L.h * 2);
+  return s;
+}
+constexpr int MAX_STACK_LAYERS = 1024;
+
 }  // namespace
 
 extern "C" {
@@ -280,121 +599,20 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
                      void* const* streams, int nstreams) {
   Layout L;
   TRY(validate(cfg, &L));
-  TRY(check_params(L, P));
+  const FwdLayer B{P, x, attn_others, mlp_others, attn_partial, mlp_partial, y, saved};
+  TRY(check_fwd_layer(L, B));
   TRY(check_streams(streams, nstreams));
-  if (!x || !attn_partial || !mlp_partial || !saved) return fail(DOMINO_ERR_NULL_POINTER, "x, attn_partial, mlp_partial or saved is NULL");
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
   g_sync_used = 0;
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
-  const int ns = nstreams;
-  hipStream_t s0 = as_stream(streams[0]);
-  const int nslice = L.p < ns ? L.p : ns;                  // streams that carry row slices
-  const bool wide = ns >= L.p * L.q;                        // enough streams for every column piece
-  auto piece_stream = [&](int i, int j) { return (wide && j > 0) ? i + j * L.p : i % nslice; };
-  std::vector<char> used(ns, 0);
-  for (int i = 0; i < L.p; ++i)
-    for (int j = 0; j < L.q; ++j) used[piece_stream(i, j)] = 1;
-  {  // fork: one event on streams[0], every other stream of this call waits for it
-    hipEvent_t fork;
-    TRY(next_sync_event(&fork));
-    HIP_TRY(hipEventRecord(fork, s0), "hipEventRecord");
-    for (int k = 1; k < ns; ++k)
-      if (used[k]) HIP_TRY(hipStreamWaitEvent(as_stream(streams[k]), fork, 0), "hipStreamWaitEvent");
-  }
-
-  const int Ms = L.Ms;
-  const bool rms = L.llama;
-  for (int i = 0; i < L.p; ++i) {
-    hipStream_t st = as_stream(streams[i % nslice]);
-    const size_t r0 = (size_t)i * Ms;                       // first token row of the slice
-    const size_t rh = r0 * L.h * 2;                         // byte offset into [M, h] bf16 tensors
-    const char* xi = at(x, rh);
-    char* ln1 = at(saved, L.ln1 + rh);
-    char* qkv = at(saved, L.qkv + r0 * 3 * L.hl * 2);
-    char* ctx = at(saved, L.ctx + r0 * L.hl * 2);
-    float* lse = reinterpret_cast<float*>(at(saved, L.lse)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
-    char* x1 = at(saved, L.x1 + rh);
-    char* ln2 = at(saved, L.ln2 + rh);
-    char* pre = at(saved, L.pre + r0 * L.upc * 2);
-    char* act = at(saved, L.act + r0 * L.fl * 2);
-    float* mean1 = reinterpret_cast<float*>(at(saved, L.mean1)) + r0;
-    float* rstd1 = reinterpret_cast<float*>(at(saved, L.rstd1)) + r0;
-    float* mean2 = reinterpret_cast<float*>(at(saved, L.mean2)) + r0;
-    float* rstd2 = reinterpret_cast<float*>(at(saved, L.rstd2)) + r0;
-
-    {  // F1: Norm1
-      ProfScope ps(PC_NORM_FWD, st);
-      NormFwdArgs a{};
-      a.x = xi; a.gamma = P->norm1_g; a.beta = P->norm1_b; a.y = ln1; a.mean = rms ? nullptr : mean1; a.rstd = rstd1;
-      a.rows = Ms; a.h = L.h; a.rms = rms; a.eps = cfg->norm_eps;
-      LAUNCH(norm_fwd_launch(a, st), "norm1 forward");
-    }
-    {  // F2: X * A (attention), column-parallel, never column-sliced
-      ProfScope ps(PC_GEMM_QKV, st);
-      GemmArgs a = gemm_args(ln1, L.h, P->w_qkv, 3 * L.hl, qkv, 3 * L.hl, Ms, 3 * L.hl, L.h);
-      a.bias = P->b_qkv;
-      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "qkv product");
-    }
-    if (L.llama) {
-      ProfScope ps(PC_ROPE, st);
-      LAUNCH(rope_launch(qkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 0, st), "rotary embedding");
-    }
-    {  // F3
-      ProfScope ps(PC_ATTN_FWD, st);
-      AttnArgs a{};
-      a.qkv = qkv; a.ld = 3 * L.hl; a.ctx = ctx; a.ld_ctx = L.hl; a.lse = lse;
-      a.batch = L.b / L.p; a.seq = L.s; a.heads = L.nl; a.head_dim = L.d; a.scale = 1.0f / sqrtf((float)L.d);
-      LAUNCH(attention_fwd_launch(a, st), "attention forward");
-    }
-    // F4: (XA) * B_j, one piece per column slice, written in place into the full-width buffer
-    for (int j = 0; j < L.q; ++j) {
-      hipStream_t sj = as_stream(streams[piece_stream(i, j)]);
-      TRY(edge(st, sj));
-      {
-        ProfScope ps(PC_GEMM_OUT, sj);
-        const size_t cj = (size_t)j * L.hq * 2;
-        GemmArgs a = gemm_args(ctx, L.hl, at(P->w_o, cj), L.h, at(attn_partial, rh + cj), L.h, Ms, L.hq, L.hl);
-        LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "out-projection piece");
-      }
-      TRY(edge(sj, st));                                    // column synchronisation before Norm2
-    }
-    {  // F5: residual + reduced attention output + Norm2
-      ProfScope ps(PC_NORM_FWD, st);
-      NormFwdArgs a{};
-      a.x = xi; a.add1 = at(attn_partial, rh); a.add2 = attn_others ? at(attn_others, rh) : nullptr; a.vec = P->b_o;
-      a.gamma = P->norm2_g; a.beta = P->norm2_b; a.xsum = x1; a.y = ln2; a.mean = rms ? nullptr : mean2; a.rstd = rstd2;
-      a.rows = Ms; a.h = L.h; a.rms = rms; a.eps = cfg->norm_eps;
-      LAUNCH(norm_fwd_launch(a, st), "norm2 forward");
-    }
-    {  // F6: X * A (MLP) with the activation fused
-      ProfScope ps(PC_GEMM_UP, st);
-      GemmArgs a = gemm_args(ln2, L.h, P->w_up, L.upc, act, L.fl, Ms, L.fl, L.h);
-      a.aux = pre; a.ldaux = L.upc; a.gelu_tanh = cfg->gelu_tanh;
-      if (L.llama) { a.n_split = L.fl; LAUNCH(gemm_launch(GEMM_NN, EPI_SWIGLU, a, -1, st), "mlp-up product"); }
-      else { a.bias = P->b_up; LAUNCH(gemm_launch(GEMM_NN, EPI_BIAS_GELU, a, -1, st), "mlp-up product"); }
-    }
-    for (int j = 0; j < L.q; ++j) {  // F7
-      hipStream_t sj = as_stream(streams[piece_stream(i, j)]);
-      TRY(edge(st, sj));
-      {
-        ProfScope ps(PC_GEMM_DOWN, sj);
-        const size_t cj = (size_t)j * L.hq * 2;
-        GemmArgs a = gemm_args(act, L.fl, at(P->w_down, cj), L.h, at(mlp_partial, rh + cj), L.h, Ms, L.hq, L.fl);
-        LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "mlp-down piece");
-      }
-      TRY(edge(sj, st));
-    }
-    if (y) {  // F8
-      ProfScope ps(PC_RESID_OUT, st);
-      LAUNCH(residual_out_launch(x1, at(mlp_partial, rh), mlp_others ? at(mlp_others, rh) : nullptr, P->b_down,
-                                 at(y, rh), (long)Ms * L.h, L.h, st), "block output");
-    }
-  }
-  for (int k = 1; k < ns; ++k)
-    if (used[k]) TRY(edge(as_stream(streams[k]), s0));
+  const StreamPlan S(streams, nstreams, L.p, L.q);
+  const std::vector<char> used = S.used_fwd();
+  TRY(fork_streams(S, used));
+  for (int i = 0; i < L.p; ++i) TRY(enqueue_fwd_slice(L, cfg, S, B, i));
+  TRY(join_streams(S, used));
   return DOMINO_OK;
 }
 
@@ -408,160 +626,106 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
                      void* const* streams, int nstreams) {
   Layout L;
   TRY(validate(cfg, &L));
-  TRY(check_params(L, P));
+  BwdLayer B{P, G, saved, x, dy, dln2_others, dln1_others, dln2_partial, dln1_partial, dx, nullptr, accumulate};
+  TRY(check_bwd_layer(L, B));
   TRY(check_streams(streams, nstreams));
-  if (!saved || !x || !dy || !dln2_partial || !dln1_partial || !dx || !G)
-    return fail(DOMINO_ERR_NULL_POINTER, "saved, x, dy, dln2_partial, dln1_partial, dx or grads is NULL");
-  if (!G->norm1_g || !G->norm2_g || !G->w_qkv || !G->w_o || !G->w_up || !G->w_down)
-    return fail(DOMINO_ERR_NULL_POINTER, "a weight or norm-gain gradient pointer is NULL");
-  if (!L.llama && (!G->norm1_b || !G->norm2_b || !G->b_qkv || !G->b_o || !G->b_up || !G->b_down))
-    return fail(DOMINO_ERR_NULL_POINTER, "a GPT bias or norm-shift gradient pointer is NULL");
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
   g_sync_used = 0;
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
-  const int ns = nstreams;
-  hipStream_t s0 = as_stream(streams[0]);
-  const int nused = L.p < ns ? L.p : ns;
-  {  // fork: one event on streams[0], every other slice stream waits for it
-    hipEvent_t fork;
-    TRY(next_sync_event(&fork));
-    HIP_TRY(hipEventRecord(fork, s0), "hipEventRecord");
-    for (int k = 1; k < nused; ++k) HIP_TRY(hipStreamWaitEvent(as_stream(streams[k]), fork, 0), "hipStreamWaitEvent");
+  B.red = reinterpret_cast<float*>(at(workspace, L.red));
+  const StreamPlan S(streams, nstreams, L.p, 1);            // the backward uses the slice streams only
+  const std::vector<char> used = S.used_fwd();
+  TRY(fork_streams(S, used));
+  WgChain wg;
+  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), B, i, wg));
+  TRY(join_streams(S, used));
+  TRY(enqueue_vector_grads(L, B, as_stream(streams[0])));
+  return DOMINO_OK;
+}
+
+// ------------------------------------------------------------------------------------ stack of blocks
+size_t domino_stack_workspace_bytes(const domino_cfg* cfg, int nlayers) {
+  Layout L;
+  if (validate(cfg, &L) != DOMINO_OK) return 0;
+  if (nlayers < 1 || nlayers > MAX_STACK_LAYERS) { fail(DOMINO_ERR_INVALID_ARG, "nlayers %d outside [1, %d]", nlayers, MAX_STACK_LAYERS); return 0; }
+  return stack_layout(L, nlayers).total;
+}
+
+int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* x,
+                     const domino_stack_fwd_io* io, void* workspace, size_t workspace_bytes,
+                     void* const* streams, int nstreams) {
+  Layout L;
+  TRY(validate(cfg, &L));
+  if (nlayers < 1 || nlayers > MAX_STACK_LAYERS) return fail(DOMINO_ERR_INVALID_ARG, "nlayers %d outside [1, %d]", nlayers, MAX_STACK_LAYERS);
+  if (!params || !io) return fail(DOMINO_ERR_NULL_POINTER, "params or io is NULL");
+  std::vector<FwdLayer> layers(nlayers);
+  for (int l = 0; l < nlayers; ++l) {
+    layers[l] = FwdLayer{&params[l], l == 0 ? x : io[l - 1].y, io[l].attn_others, io[l].mlp_others,
+                         io[l].attn_partial, io[l].mlp_partial, io[l].y, io[l].saved};
+    TRY(check_fwd_layer(L, layers[l]));
+    if (!io[l].y) return fail(DOMINO_ERR_NULL_POINTER, "y of block %d is NULL: a stack needs every block's output", l);
   }
+  TRY(check_streams(streams, nstreams));
+  const size_t need = stack_layout(L, nlayers).total;
+  if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
+  if (workspace_bytes < need) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
+  std::lock_guard<std::mutex> lock(g_mutex);
+  g_sync_used = 0;
+  ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
-  const int Ms = L.Ms;
-  const bool rms = L.llama;
-  void* ws = workspace;
-  hipStream_t prev = nullptr;     // stream of the previous slice: its weight gradients come first
-  hipEvent_t wg_prev[4] = {}, wg_cur[4] = {};
-  for (int i = 0; i < L.p; ++i) {
-    hipStream_t st = as_stream(streams[i % ns]);
-    const size_t r0 = (size_t)i * Ms;
-    const size_t rh = r0 * L.h * 2;
-    const char* xi = at(x, rh);
-    const char* dyi = at(dy, rh);
-    const char* ln1 = at(saved, L.ln1 + rh);
-    const char* qkv = at(saved, L.qkv + r0 * 3 * L.hl * 2);
-    const char* ctx = at(saved, L.ctx + r0 * L.hl * 2);
-    const float* lse = reinterpret_cast<const float*>(at(saved, L.lse)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
-    const char* x1 = at(saved, L.x1 + rh);
-    const char* ln2 = at(saved, L.ln2 + rh);
-    const char* pre = at(saved, L.pre + r0 * L.upc * 2);
-    const char* act = at(saved, L.act + r0 * L.fl * 2);
-    const float* mean1 = reinterpret_cast<const float*>(at(saved, L.mean1)) + r0;
-    const float* rstd1 = reinterpret_cast<const float*>(at(saved, L.rstd1)) + r0;
-    const float* mean2 = reinterpret_cast<const float*>(at(saved, L.mean2)) + r0;
-    const float* rstd2 = reinterpret_cast<const float*>(at(saved, L.rstd2)) + r0;
-    char* d_pre = at(ws, L.d_pre + r0 * L.upc * 2);
-    char* dx1 = at(ws, L.dx1 + rh);
-    char* dctx = at(ws, L.dctx + r0 * L.hl * 2);
-    char* dqkv = at(ws, L.dqkv + r0 * 3 * L.hl * 2);
-    float* dot = reinterpret_cast<float*>(at(ws, L.dot)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
-    float* red = reinterpret_cast<float*>(at(ws, L.red)) + (size_t)i * L.red_floats;
-    auto area = [&](int k) { return red + L.area_off[k]; };
-    const int beta = (i > 0 || accumulate) ? 1 : 0;
-    const bool chain = prev && prev != st;      // weight gradients are summed over slices in slice order
+  // a row slice of block l+1 needs only the same row slice of block l (Sec. 3.2): the slices run through the
+  // whole stack on their own streams and meet only at the end
+  const StreamPlan S(streams, nstreams, L.p, L.q);
+  const std::vector<char> used = S.used_fwd();
+  TRY(fork_streams(S, used));
+  for (int l = 0; l < nlayers; ++l)
+    for (int i = 0; i < L.p; ++i) TRY(enqueue_fwd_slice(L, cfg, S, layers[l], i));
+  TRY(join_streams(S, used));
+  return DOMINO_OK;
+}
 
-    auto wgrad = [&](int which, int cls, const void* A, long lda, const void* B, long ldb, float* C, long ldc,
-                     int M, int N) -> int {
-      if (chain) HIP_TRY(hipStreamWaitEvent(st, wg_prev[which], 0), "hipStreamWaitEvent");
-      {
-        ProfScope ps(cls, st);
-        GemmArgs a = gemm_args(A, lda, B, ldb, C, ldc, M, N, Ms);
-        a.beta = beta;
-        LAUNCH(gemm_launch(GEMM_TN, EPI_ACC_F32, a, -1, st), "weight gradient");
-      }
-      TRY(next_sync_event(&wg_cur[which]));
-      HIP_TRY(hipEventRecord(wg_cur[which], st), "hipEventRecord");
-      return DOMINO_OK;
-    };
-    auto colsum = [&](const void* g, long ld, int n, int k) -> int {
-      ProfScope ps(PC_COLSUM, st);
-      LAUNCH(colsum_partial_launch(g, ld, Ms, n, area(k), st), "bias gradient");
-      return DOMINO_OK;
-    };
-    auto norm_bwd = [&](const void* ga, const void* gb, const void* xin, const void* gamma, const float* mean,
-                        const float* rstd, const void* dres, void* out, int kg, int kb, int kres = -1, int kdx = -1) -> int {
-      ProfScope ps(PC_NORM_BWD, st);
-      NormBwdArgs a{};
-      a.ga = ga; a.gb = gb; a.x = xin; a.gamma = gamma; a.mean = mean; a.rstd = rstd; a.dres = dres; a.dx = out;
-      a.part_g = area(kg); a.part_b = area(kb); a.rows = Ms; a.h = L.h; a.rms = rms;
-      if (kres >= 0) { a.part_dres = area(kres); a.part_dx = area(kdx); }   // bias gradients of the two row-cut products
-      LAUNCH(norm_bwd_launch(a, st), "norm backward");
-      return DOMINO_OK;
-    };
-
-    {  // B1 + B3: input gradient of the down-projection (all q column slices inside the K loop), activation backward fused
-      ProfScope ps(PC_DGRAD_DOWN, st);
-      GemmArgs a = gemm_args(dyi, L.h, P->w_down, L.h, d_pre, L.upc, Ms, L.fl, L.h);
-      a.aux = const_cast<char*>(pre); a.ldaux = L.upc; a.gelu_tanh = cfg->gelu_tanh;
-      if (L.llama) { a.n_split = L.fl; LAUNCH(gemm_launch(GEMM_NT, EPI_DSWIGLU, a, -1, st), "mlp-down input gradient"); }
-      else LAUNCH(gemm_launch(GEMM_NT, EPI_DGELU, a, -1, st), "mlp-down input gradient");
-    }
-    TRY(wgrad(0, PC_WGRAD_DOWN, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
-    {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
-      ProfScope ps(PC_DGRAD_UP, st);
-      GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(dln2_partial, rh), L.h, Ms, L.h, L.upc);
-      LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "mlp-up input gradient");
-    }
-    TRY(wgrad(1, PC_WGRAD_UP, ln2, L.h, d_pre, L.upc, G->w_up, L.upc, L.h, L.upc));
-    if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, AREA_BUP));
-    // B5
-    TRY(norm_bwd(at(dln2_partial, rh), dln2_others ? at(dln2_others, rh) : nullptr, x1, P->norm2_g, mean2, rstd2,
-                 dyi, dx1, AREA_G2, AREA_B2, L.llama ? -1 : AREA_BDOWN, L.llama ? -1 : AREA_BO));
-    {  // B6
-      ProfScope ps(PC_DGRAD_OUT, st);
-      GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
-      LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "out-projection input gradient");
-    }
-    TRY(wgrad(2, PC_WGRAD_OUT, ctx, L.hl, dx1, L.h, G->w_o, L.h, L.hl, L.h));
-    {  // B7
-      ProfScope ps(PC_ATTN_BWD, st);
-      AttnArgs a{};
-      a.qkv = qkv; a.ld = 3 * L.hl; a.ctx = const_cast<char*>(ctx); a.ld_ctx = L.hl; a.dctx = dctx;
-      a.lse = const_cast<float*>(lse); a.dot = dot; a.dqkv = dqkv;
-      a.batch = L.b / L.p; a.seq = L.s; a.heads = L.nl; a.head_dim = L.d; a.scale = 1.0f / sqrtf((float)L.d);
-      LAUNCH(attention_bwd_launch(a, st), "attention backward");
-    }
-    if (L.llama) {
-      ProfScope ps(PC_ROPE, st);
-      LAUNCH(rope_launch(dqkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 1, st), "rotary embedding backward");
-    }
-    {  // B8: input gradient of QKV: the tensor the fourth all-reduce would sum
-      ProfScope ps(PC_DGRAD_QKV, st);
-      GemmArgs a = gemm_args(dqkv, 3 * L.hl, P->w_qkv, 3 * L.hl, at(dln1_partial, rh), L.h, Ms, L.h, 3 * L.hl);
-      LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "qkv input gradient");
-    }
-    TRY(wgrad(3, PC_WGRAD_QKV, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
-    if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, AREA_BQKV));
-    TRY(norm_bwd(at(dln1_partial, rh), dln1_others ? at(dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
-                 dx1, at(dx, rh), AREA_G1, AREA_B1));
-
-    prev = st;
-    for (int k = 0; k < 4; ++k) wg_prev[k] = wg_cur[k];
+int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* dy,
+                     const domino_stack_bwd_io* io, void* dx, const domino_grads* grads, int accumulate,
+                     void* workspace, size_t workspace_bytes, void* const* streams, int nstreams) {
+  Layout L;
+  TRY(validate(cfg, &L));
+  if (nlayers < 1 || nlayers > MAX_STACK_LAYERS) return fail(DOMINO_ERR_INVALID_ARG, "nlayers %d outside [1, %d]", nlayers, MAX_STACK_LAYERS);
+  if (!params || !io || !grads) return fail(DOMINO_ERR_NULL_POINTER, "params, io or grads is NULL");
+  if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
+  const StackLayout SL = stack_layout(L, nlayers);
+  if (workspace_bytes < SL.total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, SL.total);
+  void* dmid = at(workspace, SL.dmid);
+  std::vector<BwdLayer> layers(nlayers);
+  for (int l = 0; l < nlayers; ++l) {
+    float* red = reinterpret_cast<float*>(l == 0 ? at(workspace, L.red) : at(workspace, SL.extra_red + (size_t)(l - 1) * SL.red_bytes));
+    // the gradient handed down the stack lives in one tensor: a slice's last kernel of block l writes the rows
+    // that the same slice of block l-1, next on the same stream, reads
+    layers[l] = BwdLayer{&params[l], &grads[l], io[l].saved, io[l].x, l == nlayers - 1 ? dy : dmid,
+                         io[l].dln2_others, io[l].dln1_others, io[l].dln2_partial, io[l].dln1_partial,
+                         l == 0 ? dx : dmid, red, accumulate};
+    TRY(check_bwd_layer(L, layers[l]));
   }
-  for (int k = 1; k < nused; ++k) TRY(edge(as_stream(streams[k]), s0));
+  TRY(check_streams(streams, nstreams));
+  std::lock_guard<std::mutex> lock(g_mutex);
+  g_sync_used = 0;
+  ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
-  // vector gradients: one launch sums, for every vector, the partial rows of all slices in slice order
-  {
-    ProfScope ps(PC_COLSUM, s0);
-    float* red0 = reinterpret_cast<float*>(at(ws, L.red));
-    struct { int k; float* out; } vec[NAREAS] = {
-      {AREA_G1, G->norm1_g}, {AREA_B1, G->norm1_b}, {AREA_G2, G->norm2_g}, {AREA_B2, G->norm2_b},
-      {AREA_BQKV, G->b_qkv}, {AREA_BO, G->b_o}, {AREA_BUP, G->b_up}, {AREA_BDOWN, G->b_down}};
-    ColsumJobs jobs{};
-    int njobs = 0;
-    for (auto& v : vec) {
-      if (!v.out) continue;
-      if (L.llama && v.k != AREA_G1 && v.k != AREA_G2) continue;
-      jobs.job[njobs++] = {red0 + L.area_off[v.k], v.out, L.area_rows[v.k], L.area_n[v.k], (long)L.area_n[v.k],
-                           L.p, (long)L.red_floats};
-    }
-    LAUNCH(colsum_finish_jobs_launch(jobs, njobs, accumulate, s0), "vector gradient reduction");
+  const StreamPlan S(streams, nstreams, L.p, 1);
+  const std::vector<char> used = S.used_fwd();
+  TRY(fork_streams(S, used));
+  hipStream_t last = S.slice(L.p - 1);
+  for (int l = nlayers - 1; l >= 0; --l) {
+    WgChain wg;
+    for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), layers[l], i, wg));
+    // the block's vector gradients need every slice: they go on the last slice's stream, which the chain of
+    // weight gradients already makes the last to finish the block
+    for (int k = 0; k < S.nslice; ++k) TRY(edge(as_stream(streams[k]), last));
+    TRY(enqueue_vector_grads(L, layers[l], last));
   }
+  TRY(join_streams(S, used));
   return DOMINO_OK;
 }
 

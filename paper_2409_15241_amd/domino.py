@@ -25,7 +25,8 @@ PARAM_NAMES = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "norm2_g", "norm2_b", "w_up", "b_up", "w_down", "b_down")
 EXPORTS = (
     "domino_validate_cfg", "domino_saved_bytes", "domino_workspace_bytes", "domino_saved_slot",
-    "domino_layer_fwd", "domino_layer_bwd", "domino_gemm", "domino_norm_fwd",
+    "domino_layer_fwd", "domino_layer_bwd", "domino_stack_workspace_bytes", "domino_stack_fwd", "domino_stack_bwd",
+    "domino_gemm", "domino_norm_fwd",
     "domino_norm_bwd_scratch_floats", "domino_norm_bwd", "domino_attention_fwd", "domino_attention_bwd",
     "domino_rope", "domino_colsum", "domino_profile_enable", "domino_profile_classes",
     "domino_profile_name", "domino_profile_read", "domino_profile_reset", "domino_last_error",
@@ -50,6 +51,18 @@ class domino_params(C.Structure):
 
 class domino_grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES]
+
+
+STACK_FWD_FIELDS = ("attn_others", "mlp_others", "attn_partial", "mlp_partial", "y", "saved")
+STACK_BWD_FIELDS = ("x", "saved", "dln2_others", "dln1_others", "dln2_partial", "dln1_partial")
+
+
+class domino_stack_fwd_io(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in STACK_FWD_FIELDS]
+
+
+class domino_stack_bwd_io(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in STACK_BWD_FIELDS]
 
 
 _lib: Optional[C.CDLL] = None
@@ -77,6 +90,11 @@ def load() -> C.CDLL:
         "domino_layer_fwd": (i32, [cfgp, C.POINTER(domino_params), vp, vp, vp, vp, vp, vp, vp, vp, sz,
                                    C.POINTER(vp), i32]),
         "domino_layer_bwd": (i32, [cfgp, C.POINTER(domino_params), vp, vp, vp, vp, vp, vp, vp, vp,
+                                   C.POINTER(domino_grads), i32, vp, sz, C.POINTER(vp), i32]),
+        "domino_stack_workspace_bytes": (sz, [cfgp, i32]),
+        "domino_stack_fwd": (i32, [cfgp, i32, C.POINTER(domino_params), vp, C.POINTER(domino_stack_fwd_io), vp, sz,
+                                   C.POINTER(vp), i32]),
+        "domino_stack_bwd": (i32, [cfgp, i32, C.POINTER(domino_params), vp, C.POINTER(domino_stack_bwd_io), vp,
                                    C.POINTER(domino_grads), i32, vp, sz, C.POINTER(vp), i32]),
         "domino_gemm": (i32, [i32, i32, i32, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, vp, i64, i32, i32, i32, vp]),
         "domino_norm_fwd": (i32, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]),
@@ -197,6 +215,38 @@ def domino_layer_bwd(cfg, params, saved, x, dy, dln2_others, dln1_others, dln2_p
     _check(load().domino_layer_bwd(C.byref(cfg), C.byref(ps), _ptr(saved), _ptr(x), _ptr(dy), _ptr(dln2_others),
                                    _ptr(dln1_others), _ptr(dln2_partial), _ptr(dln1_partial), _ptr(dx),
                                    C.byref(gs), int(accumulate), _ptr(workspace), ws_bytes, arr, n))
+
+
+# --------------------------------------------------------------------------- a stack of blocks
+def domino_stack_workspace_bytes(cfg: domino_cfg, nlayers: int) -> int:
+    return load().domino_stack_workspace_bytes(C.byref(cfg), nlayers)
+
+
+def _struct_array(cls, fields, dicts):
+    return (cls * len(dicts))(*[cls(**{n: _ptr(d.get(n)) for n in fields}) for d in dicts])
+
+
+def _params_array(cls, dicts):
+    return (cls * len(dicts))(*[_params_struct(cls, d) for d in dicts])
+
+
+def domino_stack_fwd(cfg, params, x, io, workspace, streams) -> None:
+    """params: one dict of the twelve tensors per block; io: one dict per block keyed by STACK_FWD_FIELDS."""
+    arr, n = _streams(streams)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().domino_stack_fwd(C.byref(cfg), len(params), _params_array(domino_params, params), _ptr(x),
+                                   _struct_array(domino_stack_fwd_io, STACK_FWD_FIELDS, io), _ptr(workspace),
+                                   ws_bytes, arr, n))
+
+
+def domino_stack_bwd(cfg, params, dy, io, dx, grads, accumulate, workspace, streams) -> None:
+    """io: one dict per block keyed by STACK_BWD_FIELDS; grads: one dict of fp32 tensors per block."""
+    arr, n = _streams(streams)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().domino_stack_bwd(C.byref(cfg), len(params), _params_array(domino_params, params), _ptr(dy),
+                                   _struct_array(domino_stack_bwd_io, STACK_BWD_FIELDS, io), _ptr(dx),
+                                   _params_array(domino_grads, grads), int(accumulate), _ptr(workspace), ws_bytes,
+                                   arr, n))
 
 
 # --------------------------------------------------------------------------- single kernels

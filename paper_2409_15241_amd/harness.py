@@ -79,3 +79,54 @@ class LayerBuffers:
         if name in ("lse", "mean1", "rstd1", "mean2", "rstd2"):
             return raw.view(torch.float32)
         return raw.view(torch.bfloat16)
+
+
+class StackBuffers:
+    """A stack of blocks of one configuration, resident on the GPU: per block its parameters, the four
+    stand-ins of the other ranks' sums, the four partial outputs, y, the saved activations and the gradients."""
+
+    def __init__(self, sc: synth.ShardConfig, params, x: np.ndarray, dy: np.ndarray, others=None,
+                 nstreams: int = 4, device: str = "cuda:0"):
+        self.sc = sc
+        self.cfg = domino.make_cfg(sc)
+        rc = domino.domino_validate_cfg(self.cfg)
+        if rc != domino.OK:
+            raise domino.DominoError(rc, domino.domino_last_error())
+        self.device = torch.device(device)
+        dev = self.device
+        self.nlayers = len(params)
+        self.params = [{k: to_device_bf16(v, dev) for k, v in P.items()} for P in params]
+        self.x = to_device_bf16(x, dev)
+        self.dy = to_device_bf16(dy, dev)
+        others = others or [{} for _ in params]
+        self.others = [{k: to_device_bf16(v, dev) for k, v in o.items()} for o in others]
+        shape = (sc.batch, sc.seq, sc.hidden)
+        mk = lambda: torch.empty(shape, dtype=torch.bfloat16, device=dev)
+        nbytes = domino.domino_saved_bytes(self.cfg)
+        self.out = [dict(attn_partial=mk(), mlp_partial=mk(), y=mk(), dln2_partial=mk(), dln1_partial=mk(),
+                         saved=torch.empty(nbytes, dtype=torch.uint8, device=dev)) for _ in params]
+        self.dx = mk()
+        self.workspace = torch.empty(domino.domino_stack_workspace_bytes(self.cfg, self.nlayers), dtype=torch.uint8,
+                                     device=dev)
+        self.grads = [{k: (None if v is None else torch.zeros(v.shape, dtype=torch.float32, device=dev))
+                       for k, v in P.items()} for P in self.params]
+        self.streams = [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
+        torch.cuda.synchronize(dev)     # uploads ran on torch's current stream, which the pool does not wait for
+
+    def layer_input(self, l: int) -> torch.Tensor:
+        return self.x if l == 0 else self.out[l - 1]["y"]
+
+    def forward(self) -> None:
+        io = [dict(attn_others=o.get("attn_others"), mlp_others=o.get("mlp_others"), attn_partial=b["attn_partial"],
+                   mlp_partial=b["mlp_partial"], y=b["y"], saved=b["saved"]) for o, b in zip(self.others, self.out)]
+        domino.domino_stack_fwd(self.cfg, self.params, self.x, io, self.workspace, self.streams)
+
+    def backward(self, accumulate: bool = False) -> None:
+        io = [dict(x=self.layer_input(l), saved=b["saved"], dln2_others=o.get("dln2_others"),
+                   dln1_others=o.get("dln1_others"), dln2_partial=b["dln2_partial"], dln1_partial=b["dln1_partial"])
+              for l, (o, b) in enumerate(zip(self.others, self.out))]
+        domino.domino_stack_bwd(self.cfg, self.params, self.dy, io, self.dx, self.grads, accumulate, self.workspace,
+                                self.streams)
+
+    def sync(self) -> None:
+        torch.cuda.synchronize(self.device)

@@ -196,3 +196,16 @@ def make_rank_params(cfg: ShardConfig, rank: int | None = None, seed: int | None
         P["b_o"] = np.zeros(h, np.float32)
         P["b_down"] = np.zeros(h, np.float32)
     return P
+
+
+LAYER_SEED_STRIDE = 7919
+
+
+def make_stack(cfg: ShardConfig, nlayers: int, rank: int | None = None, random_affine: bool = False,
+               std: float = 0.02, others_scale: float = 0.5):
+    """Parameters and all-reduce stand-ins of ``nlayers`` blocks: block l draws from seed + l * 7919."""
+    base = config_seed(cfg)
+    params = [make_rank_params(cfg, rank, seed=base + l * LAYER_SEED_STRIDE, random_affine=random_affine, std=std)
+              for l in range(nlayers)]
+    others = [make_others(cfg, seed=base + l * LAYER_SEED_STRIDE, scale=others_scale) for l in range(nlayers)]
+    return params, others

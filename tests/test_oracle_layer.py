@@ -215,6 +215,61 @@ def test_full_layer_matches_torch_autograd_composition(base):
             assert rel(g, ft[k].grad.numpy()) < 1e-11, k
 
 
+def _f64(d):
+    return {k: (None if v is None else v.astype(np.float64)) for k, v in d.items()}
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+def test_stack_matches_torch_autograd_composition(base):
+    """Three blocks, unsharded (t = 1, no other ranks): forward output, input gradient and every
+    block's parameter gradients against autograd through three composed library-routine blocks."""
+    cfg = small(base).replace(tp=1, rank=0)
+    params, _ = synth.make_stack(cfg, 3, random_affine=True, std=0.2)
+    Ps = [_f64(P) for P in params]
+    x, dy = (a.astype(np.float64) for a in synth.make_activations(cfg))
+    Fo = O.rank_stack_fwd(cfg, Ps, x)
+    Bo = O.rank_stack_bwd(cfg, Ps, Fo, dy)
+    fts = [{k: (None if v is None else torch.tensor(v, requires_grad=True)) for k, v in P.items()} for P in Ps]
+    xt = torch.tensor(x, requires_grad=True)
+    cur = xt
+    for l, ft in enumerate(fts):
+        cur = _torch_layer(cfg, ft, cur)
+        assert rel(Fo[l]["y"], cur.detach().numpy()) < 1e-12, l
+    cur.backward(torch.tensor(dy))
+    assert rel(Bo[0]["dx"], xt.grad.numpy()) < 1e-10
+    for l, ft in enumerate(fts):
+        for k, g in Bo[l]["grads"].items():
+            if g is not None:
+                assert rel(g, ft[k].grad.numpy()) < 1e-10, (l, k)
+
+
+def test_stack_of_a_rank_shard_by_finite_differences():
+    """A rank's two-block stack with constant forward stand-ins: directional derivative of
+    L = sum(y_last * dy) in x and in one matrix of each block; a stack of one block is the block."""
+    cfg = small(TINY)
+    params, others = synth.make_stack(cfg, 2, rank=1, random_affine=True, std=0.2)
+    Ps = [_f64(P) for P in params]
+    oth = [{k: v.astype(np.float64) for k, v in o.items() if k in ("attn_others", "mlp_others")} for o in others]
+    x, dy = (a.astype(np.float64) for a in synth.make_activations(cfg))
+    F = O.rank_stack_fwd(cfg, Ps, x, oth)
+    B = O.rank_stack_bwd(cfg, Ps, F, dy)
+    loss = lambda Pl, xx: float((O.rank_stack_fwd(cfg, Pl, xx, oth)[-1]["y"] * dy).sum())
+    rng = np.random.default_rng(5)
+    eps = 1e-6
+    v = rng.standard_normal(x.shape)
+    num = (loss(Ps, x + eps * v) - loss(Ps, x - eps * v)) / (2 * eps)
+    assert abs(num - (B[0]["dx"] * v).sum()) <= 1e-6 * max(1.0, abs(num))
+    for l, k in ((0, "w_down"), (1, "w_qkv"), (0, "norm2_g"), (1, "b_up")):
+        v = rng.standard_normal(Ps[l][k].shape)
+        Pp, Pm = [dict(P) for P in Ps], [dict(P) for P in Ps]
+        Pp[l][k], Pm[l][k] = Ps[l][k] + eps * v, Ps[l][k] - eps * v
+        num = (loss(Pp, x) - loss(Pm, x)) / (2 * eps)
+        assert abs(num - (B[l]["grads"][k] * v).sum()) <= 1e-6 * max(1.0, abs(num)), (l, k)
+    one = O.rank_stack_fwd(cfg, Ps[:1], x, oth[:1])
+    ref = O.rank_layer_fwd(cfg, Ps[0], x, oth[0]["attn_others"], oth[0]["mlp_others"])
+    assert np.array_equal(one[0]["y"], ref["y"])
+
+
 def test_algorithmic_flops_match_hand_count():
     # GPT-3-13B shard: 2*M*(h*3hl + hl*h + h*fl + fl*h) + causal attention, times 3
     cfg = synth.WORKLOADS["gpt3-13b"]
