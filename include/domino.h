@@ -115,6 +115,36 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* params, const v
                      void* workspace, size_t workspace_bytes,
                      void* const* streams, int nstreams);
 
+/* ---- the block cut at its four all-reduce points (Sec. 2.3, Fig. 2: one all-reduce after self-attention and
+ * one after the MLP in the forward, one before each in the backward).  A caller that performs the reductions
+ * itself runs the parts in order and fills the *_others inputs of the next part from the partial outputs of
+ * the part before.  Arguments as in domino_layer_fwd / domino_layer_bwd; `parts` is an OR of the flags below
+ * and must form one of the listed runs; buffers that the chosen parts neither read nor write may be NULL.
+ * saved and workspace carry state from part to part and must not be touched in between. */
+enum { DOMINO_FWD_ATTN = 1,    /* Norm1, QKV, attention, out-projection pieces -> attn_partial          */
+       DOMINO_FWD_MLP = 2,     /* x1 = x + attn_partial + attn_others + b_o, Norm2, MLP -> mlp_partial, y */
+       DOMINO_FWD_ALL = 3 };
+enum { DOMINO_BWD_MLP = 1,     /* gradients of MLP-down and MLP-up -> dln2_partial                        */
+       DOMINO_BWD_ATTN = 2,    /* Norm2 backward (dln2_partial + dln2_others), out-projection, attention,
+                                  QKV -> dln1_partial                                                    */
+       DOMINO_BWD_NORM1 = 4,   /* Norm1 backward (dln1_partial + dln1_others) -> dx; vector gradients     */
+       DOMINO_BWD_ALL = 7 };
+int domino_layer_fwd_parts(const domino_cfg* cfg, const domino_params* params,
+                           const void* x, const void* attn_others, const void* mlp_others,
+                           void* attn_partial, void* mlp_partial, void* y,
+                           void* saved, void* workspace, size_t workspace_bytes,
+                           void* const* streams, int nstreams, int parts);
+/* The gradient tensors of every matrix are complete after the part that owns the matrix; the eight vector
+ * gradients (gains, shifts, biases) are written by DOMINO_BWD_NORM1, from partial sums that the earlier
+ * parts left in the workspace.  accumulate must be the same in all parts of one backward. */
+int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* params, const void* saved,
+                           const void* x, const void* dy,
+                           const void* dln2_others, const void* dln1_others,
+                           void* dln2_partial, void* dln1_partial, void* dx,
+                           const domino_grads* grads, int accumulate,
+                           void* workspace, size_t workspace_bytes,
+                           void* const* streams, int nstreams, int parts);
+
 /* ---- a stack of blocks (Sec. 2.3: N blocks one after the other; Sec. 3.2 and 4.1.1: the row slices stay
  * independent from block to block, so slice 0 of block l+1 starts while the other slices of block l still run) --- */
 

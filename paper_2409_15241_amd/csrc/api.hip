@@ -290,17 +290,23 @@ int join_streams(const StreamPlan& S, const std::vector<char>& used) {
   return DOMINO_OK;
 }
 
-int check_fwd_layer(const Layout& L, const FwdLayer& B) {
+int check_fwd_layer(const Layout& L, const FwdLayer& B, int parts = DOMINO_FWD_ALL) {
   TRY(check_params(L, B.P));
-  if (!B.x || !B.attn_partial || !B.mlp_partial || !B.saved) return fail(DOMINO_ERR_NULL_POINTER, "x, attn_partial, mlp_partial or saved is NULL");
+  if (parts <= 0 || (parts & ~DOMINO_FWD_ALL)) return fail(DOMINO_ERR_INVALID_ARG, "forward parts %d outside [1, %d]", parts, (int)DOMINO_FWD_ALL);
+  if (!B.x || !B.attn_partial || !B.saved) return fail(DOMINO_ERR_NULL_POINTER, "x, attn_partial or saved is NULL");
+  if ((parts & DOMINO_FWD_MLP) && !B.mlp_partial) return fail(DOMINO_ERR_NULL_POINTER, "mlp_partial is NULL");
   return DOMINO_OK;
 }
 
-int check_bwd_layer(const Layout& L, const BwdLayer& B) {
+int check_bwd_layer(const Layout& L, const BwdLayer& B, int parts = DOMINO_BWD_ALL) {
   TRY(check_params(L, B.P));
   const domino_grads* G = B.G;
-  if (!B.saved || !B.x || !B.dy || !B.dln2_partial || !B.dln1_partial || !B.dx || !G)
-    return fail(DOMINO_ERR_NULL_POINTER, "saved, x, dy, dln2_partial, dln1_partial, dx or grads is NULL");
+  if (parts <= 0 || (parts & ~DOMINO_BWD_ALL)) return fail(DOMINO_ERR_INVALID_ARG, "backward parts %d outside [1, %d]", parts, (int)DOMINO_BWD_ALL);
+  if (!B.saved || !G) return fail(DOMINO_ERR_NULL_POINTER, "saved or grads is NULL");
+  if ((parts & (DOMINO_BWD_MLP | DOMINO_BWD_ATTN)) && (!B.dy || !B.dln2_partial))
+    return fail(DOMINO_ERR_NULL_POINTER, "dy or dln2_partial is NULL");
+  if ((parts & (DOMINO_BWD_ATTN | DOMINO_BWD_NORM1)) && !B.dln1_partial) return fail(DOMINO_ERR_NULL_POINTER, "dln1_partial is NULL");
+  if ((parts & DOMINO_BWD_NORM1) && (!B.x || !B.dx)) return fail(DOMINO_ERR_NULL_POINTER, "x or dx is NULL");
   if (!G->norm1_g || !G->norm2_g || !G->w_qkv || !G->w_o || !G->w_up || !G->w_down)
     return fail(DOMINO_ERR_NULL_POINTER, "a weight or norm-gain gradient pointer is NULL");
   if (!L.llama && (!G->norm1_b || !G->norm2_b || !G->b_qkv || !G->b_o || !G->b_up || !G->b_down))
@@ -310,7 +316,8 @@ int check_bwd_layer(const Layout& L, const BwdLayer& B) {
 
 // Forward of row slice i of one block (Sec. 3.2, Eq. 3): every kernel of the slice on its own stream, the q
 // column pieces of the two row-cut products (Sec. 3.3, Eq. 4) written in place into the full-width buffers.
-int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& S, const FwdLayer& B, int i) {
+int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& S, const FwdLayer& B, int i,
+                      int parts = DOMINO_FWD_ALL) {
   const domino_params* P = B.P;
   const int Ms = L.Ms;
   const bool rms = L.llama;
@@ -332,6 +339,7 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
   float* mean2 = reinterpret_cast<float*>(at(saved, L.mean2)) + r0;
   float* rstd2 = reinterpret_cast<float*>(at(saved, L.rstd2)) + r0;
 
+  if (parts & DOMINO_FWD_ATTN) {
   {  // F1: Norm1
     ProfScope ps(PC_NORM_FWD, st);
     NormFwdArgs a{};
@@ -368,6 +376,8 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
     }
     TRY(edge(sj, st));                                    // column synchronisation before Norm2
   }
+  }
+  if (!(parts & DOMINO_FWD_MLP)) return DOMINO_OK;
   {  // F5: residual + reduced attention output + Norm2
     ProfScope ps(PC_NORM_FWD, st);
     NormFwdArgs a{};
@@ -412,7 +422,7 @@ struct WgChain {
 // Backward of row slice i of one block; within the slice each input gradient is enqueued before the weight
 // gradient of the same product (Sec. 4.1.2).
 int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStream_t st, const BwdLayer& B, int i,
-                      WgChain& wg) {
+                      WgChain& wg, int parts = DOMINO_BWD_ALL) {
   const domino_params* P = B.P;
   const domino_grads* G = B.G;
   const void* saved = B.saved;
@@ -420,8 +430,8 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   const bool rms = L.llama;
   const size_t r0 = (size_t)i * Ms;
   const size_t rh = r0 * L.h * 2;
-  const char* xi = at(B.x, rh);
-  const char* dyi = at(B.dy, rh);
+  const char* xi = B.x ? at(B.x, rh) : nullptr;
+  const char* dyi = B.dy ? at(B.dy, rh) : nullptr;
   const char* ln1 = at(saved, L.ln1 + rh);
   const char* qkv = at(saved, L.qkv + r0 * 3 * L.hl * 2);
   const char* ctx = at(saved, L.ctx + r0 * L.hl * 2);
@@ -473,6 +483,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     return DOMINO_OK;
   };
 
+  if (parts & DOMINO_BWD_MLP) {
   {  // B1 + B3: input gradient of the down-projection (all q column slices inside the K loop), activation backward fused
     ProfScope ps(PC_DGRAD_DOWN, st);
     GemmArgs a = gemm_args(dyi, L.h, P->w_down, L.h, d_pre, L.upc, Ms, L.fl, L.h);
@@ -488,6 +499,8 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   }
   TRY(wgrad(1, PC_WGRAD_UP, ln2, L.h, d_pre, L.upc, G->w_up, L.upc, L.h, L.upc));
   if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, AREA_BUP));
+  }
+  if (parts & DOMINO_BWD_ATTN) {
   // B5
   TRY(norm_bwd(at(B.dln2_partial, rh), B.dln2_others ? at(B.dln2_others, rh) : nullptr, x1, P->norm2_g, mean2, rstd2,
                dyi, dx1, AREA_G2, AREA_B2, L.llama ? -1 : AREA_BDOWN, L.llama ? -1 : AREA_BO));
@@ -516,8 +529,10 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   }
   TRY(wgrad(3, PC_WGRAD_QKV, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
   if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, AREA_BQKV));
-  TRY(norm_bwd(at(B.dln1_partial, rh), B.dln1_others ? at(B.dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
-               dx1, at(B.dx, rh), AREA_G1, AREA_B1));
+  }
+  if (parts & DOMINO_BWD_NORM1)
+    TRY(norm_bwd(at(B.dln1_partial, rh), B.dln1_others ? at(B.dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
+                 dx1, at(B.dx, rh), AREA_G1, AREA_B1));
 
   wg.prev = st;
   for (int k = 0; k < 4; ++k) wg.done[k] = wg.cur[k];
@@ -597,10 +612,19 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
                      void* attn_partial, void* mlp_partial, void* y,
                      void* saved, void* workspace, size_t workspace_bytes,
                      void* const* streams, int nstreams) {
+  return domino_layer_fwd_parts(cfg, P, x, attn_others, mlp_others, attn_partial, mlp_partial, y, saved, workspace,
+                                workspace_bytes, streams, nstreams, DOMINO_FWD_ALL);
+}
+
+int domino_layer_fwd_parts(const domino_cfg* cfg, const domino_params* P,
+                           const void* x, const void* attn_others, const void* mlp_others,
+                           void* attn_partial, void* mlp_partial, void* y,
+                           void* saved, void* workspace, size_t workspace_bytes,
+                           void* const* streams, int nstreams, int parts) {
   Layout L;
   TRY(validate(cfg, &L));
   const FwdLayer B{P, x, attn_others, mlp_others, attn_partial, mlp_partial, y, saved};
-  TRY(check_fwd_layer(L, B));
+  TRY(check_fwd_layer(L, B, parts));
   TRY(check_streams(streams, nstreams));
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
@@ -611,7 +635,7 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* P,
   const StreamPlan S(streams, nstreams, L.p, L.q);
   const std::vector<char> used = S.used_fwd();
   TRY(fork_streams(S, used));
-  for (int i = 0; i < L.p; ++i) TRY(enqueue_fwd_slice(L, cfg, S, B, i));
+  for (int i = 0; i < L.p; ++i) TRY(enqueue_fwd_slice(L, cfg, S, B, i, parts));
   TRY(join_streams(S, used));
   return DOMINO_OK;
 }
@@ -624,10 +648,21 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
                      const domino_grads* G, int accumulate,
                      void* workspace, size_t workspace_bytes,
                      void* const* streams, int nstreams) {
+  return domino_layer_bwd_parts(cfg, P, saved, x, dy, dln2_others, dln1_others, dln2_partial, dln1_partial, dx, G,
+                                accumulate, workspace, workspace_bytes, streams, nstreams, DOMINO_BWD_ALL);
+}
+
+int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const void* saved,
+                           const void* x, const void* dy,
+                           const void* dln2_others, const void* dln1_others,
+                           void* dln2_partial, void* dln1_partial, void* dx,
+                           const domino_grads* G, int accumulate,
+                           void* workspace, size_t workspace_bytes,
+                           void* const* streams, int nstreams, int parts) {
   Layout L;
   TRY(validate(cfg, &L));
   BwdLayer B{P, G, saved, x, dy, dln2_others, dln1_others, dln2_partial, dln1_partial, dx, nullptr, accumulate};
-  TRY(check_bwd_layer(L, B));
+  TRY(check_bwd_layer(L, B, parts));
   TRY(check_streams(streams, nstreams));
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
@@ -640,9 +675,10 @@ int domino_layer_bwd(const domino_cfg* cfg, const domino_params* P, const void* 
   const std::vector<char> used = S.used_fwd();
   TRY(fork_streams(S, used));
   WgChain wg;
-  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), B, i, wg));
+  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), B, i, wg, parts));
   TRY(join_streams(S, used));
-  TRY(enqueue_vector_grads(L, B, as_stream(streams[0])));
+  // the partial sums of all three parts lie in the workspace by the time the last part has run
+  if (parts & DOMINO_BWD_NORM1) TRY(enqueue_vector_grads(L, B, as_stream(streams[0])));
   return DOMINO_OK;
 }
 

@@ -20,12 +20,15 @@ ERR_WORKSPACE_TOO_SMALL, ERR_UNSUPPORTED, ERR_HIP = -4, -5, -6
 ARCH_GPT, ARCH_LLAMA = 0, 1
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_STORE, EPI_BIAS_GELU, EPI_SWIGLU, EPI_DGELU, EPI_DSWIGLU, EPI_ACC_F32 = range(6)
+FWD_ATTN, FWD_MLP, FWD_ALL = 1, 2, 3
+BWD_MLP, BWD_ATTN, BWD_NORM1, BWD_ALL = 1, 2, 4, 7
 
 PARAM_NAMES = ("norm1_g", "norm1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "norm2_g", "norm2_b", "w_up", "b_up", "w_down", "b_down")
 EXPORTS = (
     "domino_validate_cfg", "domino_saved_bytes", "domino_workspace_bytes", "domino_saved_slot",
-    "domino_layer_fwd", "domino_layer_bwd", "domino_stack_workspace_bytes", "domino_stack_fwd", "domino_stack_bwd",
+    "domino_layer_fwd", "domino_layer_bwd", "domino_layer_fwd_parts", "domino_layer_bwd_parts",
+    "domino_stack_workspace_bytes", "domino_stack_fwd", "domino_stack_bwd",
     "domino_gemm", "domino_norm_fwd",
     "domino_norm_bwd_scratch_floats", "domino_norm_bwd", "domino_attention_fwd", "domino_attention_bwd",
     "domino_rope", "domino_colsum", "domino_profile_enable", "domino_profile_classes",
@@ -91,6 +94,10 @@ def load() -> C.CDLL:
                                    C.POINTER(vp), i32]),
         "domino_layer_bwd": (i32, [cfgp, C.POINTER(domino_params), vp, vp, vp, vp, vp, vp, vp, vp,
                                    C.POINTER(domino_grads), i32, vp, sz, C.POINTER(vp), i32]),
+        "domino_layer_fwd_parts": (i32, [cfgp, C.POINTER(domino_params), vp, vp, vp, vp, vp, vp, vp, vp, sz,
+                                         C.POINTER(vp), i32, i32]),
+        "domino_layer_bwd_parts": (i32, [cfgp, C.POINTER(domino_params), vp, vp, vp, vp, vp, vp, vp, vp,
+                                         C.POINTER(domino_grads), i32, vp, sz, C.POINTER(vp), i32, i32]),
         "domino_stack_workspace_bytes": (sz, [cfgp, i32]),
         "domino_stack_fwd": (i32, [cfgp, i32, C.POINTER(domino_params), vp, C.POINTER(domino_stack_fwd_io), vp, sz,
                                    C.POINTER(vp), i32]),
@@ -215,6 +222,28 @@ def domino_layer_bwd(cfg, params, saved, x, dy, dln2_others, dln1_others, dln2_p
     _check(load().domino_layer_bwd(C.byref(cfg), C.byref(ps), _ptr(saved), _ptr(x), _ptr(dy), _ptr(dln2_others),
                                    _ptr(dln1_others), _ptr(dln2_partial), _ptr(dln1_partial), _ptr(dx),
                                    C.byref(gs), int(accumulate), _ptr(workspace), ws_bytes, arr, n))
+
+
+def domino_layer_fwd_parts(cfg, params, x, attn_others, mlp_others, attn_partial, mlp_partial, y,
+                           saved, workspace, streams, parts) -> None:
+    arr, n = _streams(streams)
+    ps = _params_struct(domino_params, params)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().domino_layer_fwd_parts(C.byref(cfg), C.byref(ps), _ptr(x), _ptr(attn_others), _ptr(mlp_others),
+                                         _ptr(attn_partial), _ptr(mlp_partial), _ptr(y), _ptr(saved),
+                                         _ptr(workspace), ws_bytes, arr, n, int(parts)))
+
+
+def domino_layer_bwd_parts(cfg, params, saved, x, dy, dln2_others, dln1_others, dln2_partial, dln1_partial, dx,
+                           grads, accumulate, workspace, streams, parts) -> None:
+    arr, n = _streams(streams)
+    ps = _params_struct(domino_params, params)
+    gs = _params_struct(domino_grads, grads)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().domino_layer_bwd_parts(C.byref(cfg), C.byref(ps), _ptr(saved), _ptr(x), _ptr(dy),
+                                         _ptr(dln2_others), _ptr(dln1_others), _ptr(dln2_partial),
+                                         _ptr(dln1_partial), _ptr(dx), C.byref(gs), int(accumulate),
+                                         _ptr(workspace), ws_bytes, arr, n, int(parts)))
 
 
 # --------------------------------------------------------------------------- a stack of blocks
