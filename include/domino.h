@@ -94,7 +94,9 @@ int domino_saved_slot(const domino_cfg* cfg, const char* name, size_t* offset, s
  *   y: out [b,s,h] or NULL.   saved: out, domino_saved_bytes().   workspace: scratch.
  *   streams[0..nstreams-1]: row slice i runs on streams[i % min(nstreams, p)]; with nstreams >= p*q the
  *   column piece (i, j > 0) runs on streams[i + j*p] (forked from and joined to its slice's stream),
- *   otherwise on its slice's stream. */
+ *   otherwise on its slice's stream.  Slices overlap only if their streams sit on distinct hardware queues: create
+ *   the pool once, and let the process have more hardware queues than the pool has streams (HIP's
+ *   GPU_MAX_HW_QUEUES, read when the runtime starts). */
 int domino_layer_fwd(const domino_cfg* cfg, const domino_params* params,
                      const void* x, const void* attn_others, const void* mlp_others,
                      void* attn_partial, void* mlp_partial, void* y,

@@ -28,7 +28,7 @@ class LayerBuffers:
 
     def __init__(self, sc: synth.ShardConfig, params: Dict[str, Optional[np.ndarray]], x: np.ndarray,
                  dy: np.ndarray, others: Optional[Dict[str, np.ndarray]] = None, nstreams: int = 4,
-                 device: str = "cuda:0", want_y: bool = True):
+                 device: str = "cuda:0", want_y: bool = True, streams=None):
         self.sc = sc
         self.cfg = domino.make_cfg(sc)
         rc = domino.domino_validate_cfg(self.cfg)
@@ -53,8 +53,9 @@ class LayerBuffers:
         self.workspace = torch.empty(domino.domino_workspace_bytes(self.cfg), dtype=torch.uint8, device=dev)
         self.grads = {k: (None if v is None else torch.zeros(v.shape, dtype=torch.float32, device=dev))
                       for k, v in self.params.items()}
-        # fixed pool of streams created once and picked by index (default priority)
-        self.streams = [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
+        # fixed pool of streams created once and picked by index (default priority); a caller that builds many
+        # of these objects passes its own pool so that the streams (and their hardware queues) stay the same
+        self.streams = list(streams) if streams is not None else [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
         # the uploads and fills above were enqueued on torch's current stream, which the pool's streams
         # do not wait for: everything must have landed before the first library call reads it
         torch.cuda.synchronize(dev)

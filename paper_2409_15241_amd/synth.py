@@ -87,6 +87,16 @@ WORKLOADS: Dict[str, ShardConfig] = {
     "gpt3-13b": ShardConfig("gpt3-13b", 5120, 40, 8, 0, 4, 2, 4, 2048, 20480, ARCH_GPT, index=2),
     "llama2-7b": ShardConfig("llama2-7b", 4096, 32, 8, 0, 2, 4, 2, 4096, 11008, ARCH_LLAMA, index=3),
     "llama2-13b": ShardConfig("llama2-13b", 5120, 40, 8, 0, 4, 4, 4, 4096, 13824, ARCH_LLAMA, index=4),
+    # GPT-3 sizes of Table 1 that the list above lacks, at the same 2048-token context
+    "gpt3-6.7b": ShardConfig("gpt3-6.7b", 4096, 32, 8, 0, 2, 2, 8, 2048, 16384, ARCH_GPT, index=20),
+    "gpt3-30b": ShardConfig("gpt3-30b", 7168, 56, 8, 0, 4, 2, 4, 2048, 28672, ARCH_GPT, index=21),
+    # the evaluation's own shapes (Sec. 5.3, 5.4): sequence length 512 or 1024, micro-batch 4 to 64
+    "gpt3-13b-s512-mb4": ShardConfig("gpt3-13b-s512-mb4", 5120, 40, 8, 0, 2, 1, 4, 512, 20480, ARCH_GPT, index=22),
+    "gpt3-13b-s1024-mb16": ShardConfig("gpt3-13b-s1024-mb16", 5120, 40, 8, 0, 4, 2, 16, 1024, 20480, ARCH_GPT, index=23),
+    "gpt3-6.7b-s1024-mb32": ShardConfig("gpt3-6.7b-s1024-mb32", 4096, 32, 8, 0, 4, 2, 32, 1024, 16384, ARCH_GPT, index=24),
+    "gpt3-2.7b-s512-mb64": ShardConfig("gpt3-2.7b-s512-mb64", 2560, 32, 8, 0, 4, 2, 64, 512, 10240, ARCH_GPT, index=25),
+    "llama2-7b-s1024-mb16": ShardConfig("llama2-7b-s1024-mb16", 4096, 32, 8, 0, 4, 2, 16, 1024, 11008, ARCH_LLAMA, index=26),
+    "llama2-13b-s512-mb16": ShardConfig("llama2-13b-s512-mb16", 5120, 40, 8, 0, 4, 2, 16, 512, 13824, ARCH_LLAMA, index=27),
     # a Llama-shaped toy that the oracle finishes at once (parity / pin cases only)
     "tiny-llama": ShardConfig("tiny-llama", 256, 4, 2, 0, 2, 2, 2, 128, 704, ARCH_LLAMA, index=5),
 }

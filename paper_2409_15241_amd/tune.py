@@ -28,13 +28,31 @@ def candidates(sc, ps: Iterable[int] = (1, 2, 4, 8), qs: Iterable[int] = (1, 2, 
     return out
 
 
-def measure(sc, nstreams: int, steps: int = 10, warmup: int = 3) -> float:
+def make_data(sc):
+    """The synthetic inputs of a shard; they do not depend on p, q or the pool, so a search draws them once."""
+    from . import synth
+    x, dy = synth.make_activations(sc)
+    return synth.make_rank_params(sc), x, dy, synth.make_others(sc)
+
+
+_POOL = []
+
+
+def stream_pool(n: int):
+    """The first n streams of one pool that lives as long as the process (Sec. 4.3.1: created once, picked by
+    index), so that every measured setting runs on the same streams and hardware queues."""
+    import torch
+    while len(_POOL) < n:
+        _POOL.append(torch.cuda.Stream())
+    return _POOL[:n]
+
+
+def measure(sc, nstreams: int, steps: int = 10, warmup: int = 3, data=None) -> float:
     """Milliseconds per forward + backward of the shard `sc` (its p and q) on a pool of nstreams streams."""
     import torch
-    from . import harness, synth
-    params = synth.make_rank_params(sc)
-    x, dy = synth.make_activations(sc)
-    buf = harness.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=nstreams)
+    from . import harness
+    params, x, dy, others = data if data is not None else make_data(sc)
+    buf = harness.LayerBuffers(sc, params, x, dy, others, streams=stream_pool(nstreams))
     for _ in range(warmup):
         buf.forward()
         buf.backward(accumulate=False)
@@ -47,32 +65,38 @@ def measure(sc, nstreams: int, steps: int = 10, warmup: int = 3) -> float:
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def tune(sc, pairs: Optional[List[Tuple[int, int]]] = None, streams: Iterable[int] = (1, 2, 4),
-         steps: int = 10, warmup: int = 3):
-    """Returns (best, table): best = (p, q, nstreams, ms); table lists every measured setting."""
+def tune(sc, pairs: Optional[List[Tuple[int, int]]] = None, streams: Iterable[int] = (1, 2, 4, 8),
+         steps: int = 10, warmup: int = 3, report=None):
+    """Returns (best, table): best = (p, q, nstreams, ms); table lists every measured setting; report(row) is
+    called after each measurement."""
     table = []
+    data = make_data(sc)
     for (p, q) in (pairs if pairs is not None else candidates(sc)):
         for ns in streams:
             if ns > max(p, 1) and ns > 1:
                 continue          # more streams than row slices adds nothing (column pieces stay on their slice's stream)
-            ms = measure(sc.replace(p=p, q=q), ns, steps, warmup)
+            ms = measure(sc.replace(p=p, q=q), ns, steps, warmup, data)
             table.append((p, q, ns, ms))
+            if report:
+                report(table[-1])
     best = min(table, key=lambda r: r[3])
     return best, table
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="gpt3-13b")
+    ap.add_argument("--workload", default="gpt3-13b", help="a name of synth.WORKLOADS, or 'all'")
     ap.add_argument("--steps", type=int, default=10)
     args = ap.parse_args()
     from . import domino, synth
     domino.load()
-    sc = synth.WORKLOADS[args.workload]
-    best, table = tune(sc, steps=args.steps)
-    for (p, q, ns, ms) in table:
-        print(f"p={p} q={q} streams={ns}: {ms:8.3f} ms")
-    print(json.dumps({"workload": sc.name, "best": {"p": best[0], "q": best[1], "streams": best[2], "ms": best[3]}}))
+    names = [n for n in synth.WORKLOADS if not n.startswith("tiny")] if args.workload == "all" else [args.workload]
+    for name in names:
+        sc = synth.WORKLOADS[name]
+        best, table = tune(sc, steps=args.steps, report=lambda r: print(
+            f"{name}: p={r[0]} q={r[1]} streams={r[2]}: {r[3]:8.3f} ms", flush=True))
+        print(json.dumps({"workload": sc.name, "best": {"p": best[0], "q": best[1], "streams": best[2], "ms": best[3]},
+                          "as_configured": {"p": sc.p, "q": sc.q}}), flush=True)
 
 
 if __name__ == "__main__":
