@@ -111,6 +111,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="capture the step in a HIP graph and replay it")
     ap.add_argument("--p", type=int, default=None)
     ap.add_argument("--q", type=int, default=None)
+    ap.add_argument("--stack-layers", type=int, default=4,
+                    help="with --layers 1: also time a stack of this many blocks (0 = skip) and report it under 'stack'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-step-class timing table to stderr")
@@ -262,6 +264,27 @@ def main():
         roofline["achieved_alone"] = tot_fl / (tot_ms * 1e-3) / 1e12
         roofline["frac_alone"] = roofline["achieved_alone"] / BF16_MFMA_PEAK_TFLOPS
 
+    stack = None
+    if args.layers == 1 and args.stack_layers > 1 and not args.graph:
+        # the same blocks one after the other in one call (domino_stack_fwd / domino_stack_bwd): no fork and join
+        # between blocks, so this is the rate a model of many blocks sees; same stand-in tensors for every block
+        nl = args.stack_layers
+        params_l = [synth.make_rank_params(sc, seed=synth.config_seed(sc) + l * synth.LAYER_SEED_STRIDE) for l in range(nl)]
+        sbuf = harness.StackBuffers(sc, params_l, x, dy, [others] * nl, streams=buf.streams)   # the same pool
+        for _ in range(max(2, args.warmup // 2)):
+            sbuf.forward()
+            sbuf.backward(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nrep = max(3, args.steps // 2)
+        for _ in range(nrep):
+            sbuf.forward()
+            sbuf.backward(False)
+        torch.cuda.synchronize()
+        sms = (time.perf_counter() - t0) * 1e3 / nrep
+        stack = {"layers": nl, "ms_per_step": sms, "ms_per_layer": sms / nl,
+                 "value": algorithmic_flops(sc) * nl / (sms * 1e-3) / 1e12, "unit": "TFLOP/s"}
+
     cpu = None if args.no_cpu_baseline else cpu_baseline(sc)
 
     line = {
@@ -274,7 +297,7 @@ def main():
                    "arch": "llama" if sc.arch else "gpt", "streams": args.streams, "layers": args.layers},
         "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "algorithmic_gflop_per_step": flops / 1e9, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
-        "roofline": roofline, "cpu_baseline": cpu,
+        "stack": stack, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
 

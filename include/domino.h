@@ -173,7 +173,8 @@ size_t domino_stack_workspace_bytes(const domino_cfg* cfg, int nlayers);
 /* Forward of nlayers blocks of the same configuration, params[l] and io[l] being block l's (host arrays of
  * nlayers structs).  Row slice i of every block runs on the stream domino_layer_fwd would give it, and the
  * only joins are the column synchronisations inside a block and one join onto streams[0] after the last
- * block: no stream waits for another between blocks.  Results are bitwise those of nlayers calls of
+ * block: no stream waits for another between blocks.  Between two blocks one pass over a slice's rows forms
+ * the lower block's y and the upper block's Norm1 of it.  Results are bitwise those of nlayers calls of
  * domino_layer_fwd with y of one as x of the next. */
 int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* x,
                      const domino_stack_fwd_io* io, void* workspace, size_t workspace_bytes,

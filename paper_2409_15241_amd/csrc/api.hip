@@ -316,8 +316,10 @@ int check_bwd_layer(const Layout& L, const BwdLayer& B, int parts = DOMINO_BWD_A
 
 // Forward of row slice i of one block (Sec. 3.2, Eq. 3): every kernel of the slice on its own stream, the q
 // column pieces of the two row-cut products (Sec. 3.3, Eq. 4) written in place into the full-width buffers.
+// `norm1_done`: the block's Norm1 of this slice has already been written (by the block below, see `next`).
+// `next`: the block above in a stack; its Norm1 is then taken in the same pass that forms this block's output.
 int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& S, const FwdLayer& B, int i,
-                      int parts = DOMINO_FWD_ALL) {
+                      int parts = DOMINO_FWD_ALL, bool norm1_done = false, const FwdLayer* next = nullptr) {
   const domino_params* P = B.P;
   const int Ms = L.Ms;
   const bool rms = L.llama;
@@ -340,7 +342,7 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
   float* rstd2 = reinterpret_cast<float*>(at(saved, L.rstd2)) + r0;
 
   if (parts & DOMINO_FWD_ATTN) {
-  {  // F1: Norm1
+  if (!norm1_done) {  // F1: Norm1
     ProfScope ps(PC_NORM_FWD, st);
     NormFwdArgs a{};
     a.x = xi; a.gamma = P->norm1_g; a.beta = P->norm1_b; a.y = ln1; a.mean = rms ? nullptr : mean1; a.rstd = rstd1;
@@ -404,7 +406,16 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
     }
     TRY(edge(sj, st));
   }
-  if (B.y) {  // F8
+  if (next) {  // F8 of this block and F1 of the next in one pass over the rows: y is written and normalised at once
+    ProfScope ps(PC_NORM_FWD, st);
+    NormFwdArgs a{};
+    a.x = x1; a.add1 = at(B.mlp_partial, rh); a.add2 = B.mlp_others ? at(B.mlp_others, rh) : nullptr; a.vec = P->b_down;
+    a.gamma = next->P->norm1_g; a.beta = next->P->norm1_b; a.xsum = at(B.y, rh); a.y = at(next->saved, L.ln1 + rh);
+    a.mean = rms ? nullptr : reinterpret_cast<float*>(at(next->saved, L.mean1)) + r0;
+    a.rstd = reinterpret_cast<float*>(at(next->saved, L.rstd1)) + r0;
+    a.rows = Ms; a.h = L.h; a.rms = rms; a.eps = cfg->norm_eps;
+    LAUNCH(norm_fwd_launch(a, st), "block output + next norm1");
+  } else if (B.y) {  // F8
     ProfScope ps(PC_RESID_OUT, st);
     LAUNCH(residual_out_launch(x1, at(B.mlp_partial, rh), B.mlp_others ? at(B.mlp_others, rh) : nullptr, P->b_down,
                                at(B.y, rh), (long)Ms * L.h, L.h, st), "block output");
@@ -718,7 +729,8 @@ int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   const std::vector<char> used = S.used_fwd();
   TRY(fork_streams(S, used));
   for (int l = 0; l < nlayers; ++l)
-    for (int i = 0; i < L.p; ++i) TRY(enqueue_fwd_slice(L, cfg, S, layers[l], i));
+    for (int i = 0; i < L.p; ++i)
+      TRY(enqueue_fwd_slice(L, cfg, S, layers[l], i, DOMINO_FWD_ALL, l > 0, l + 1 < nlayers ? &layers[l + 1] : nullptr));
   TRY(join_streams(S, used));
   return DOMINO_OK;
 }

@@ -37,14 +37,13 @@ void residual_out_kernel(const u32x4* __restrict__ x1, const u32x4* __restrict__
   const u32x4 vx = x1[c], va = a[c];
   const u32x4 vb = (b ? b : x1)[c];
   const u32x4 vv = (vec ? vec : x1)[vec ? c % hch : c];
-  float f[8] = {bf16_lo(vx[0]) + bf16_lo(va[0]), bf16_hi(vx[0]) + bf16_hi(va[0]),
-                bf16_lo(vx[1]) + bf16_lo(va[1]), bf16_hi(vx[1]) + bf16_hi(va[1]),
-                bf16_lo(vx[2]) + bf16_lo(va[2]), bf16_hi(vx[2]) + bf16_hi(va[2]),
-                bf16_lo(vx[3]) + bf16_lo(va[3]), bf16_hi(vx[3]) + bf16_hi(va[3])};
+  // same association as the fused norm kernel, ((x1 + a) + b) + vec with absent operands as +0, so that a
+  // caller may fold this sum into the next block's Norm1 without changing a bit
+  float f[8];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    f[2 * e] += (b ? bf16_lo(vb[e]) : 0.0f) + (vec ? bf16_lo(vv[e]) : 0.0f);
-    f[2 * e + 1] += (b ? bf16_hi(vb[e]) : 0.0f) + (vec ? bf16_hi(vv[e]) : 0.0f);
+    f[2 * e] = ((bf16_lo(vx[e]) + bf16_lo(va[e])) + (b ? bf16_lo(vb[e]) : 0.0f)) + (vec ? bf16_lo(vv[e]) : 0.0f);
+    f[2 * e + 1] = ((bf16_hi(vx[e]) + bf16_hi(va[e])) + (b ? bf16_hi(vb[e]) : 0.0f)) + (vec ? bf16_hi(vv[e]) : 0.0f);
   }
   u32x4 o = {pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
   y[c] = o;

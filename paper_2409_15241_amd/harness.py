@@ -87,7 +87,7 @@ class StackBuffers:
     stand-ins of the other ranks' sums, the four partial outputs, y, the saved activations and the gradients."""
 
     def __init__(self, sc: synth.ShardConfig, params, x: np.ndarray, dy: np.ndarray, others=None,
-                 nstreams: int = 4, device: str = "cuda:0"):
+                 nstreams: int = 4, device: str = "cuda:0", streams=None):
         self.sc = sc
         self.cfg = domino.make_cfg(sc)
         rc = domino.domino_validate_cfg(self.cfg)
@@ -111,7 +111,7 @@ class StackBuffers:
                                      device=dev)
         self.grads = [{k: (None if v is None else torch.zeros(v.shape, dtype=torch.float32, device=dev))
                        for k, v in P.items()} for P in self.params]
-        self.streams = [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
+        self.streams = list(streams) if streams is not None else [torch.cuda.Stream(device=dev) for _ in range(nstreams)]
         torch.cuda.synchronize(dev)     # uploads ran on torch's current stream, which the pool does not wait for
 
     def layer_input(self, l: int) -> torch.Tensor:
