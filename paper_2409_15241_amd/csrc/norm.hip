@@ -1,14 +1,11 @@
 // LayerNorm / RMSNorm forward and backward with the surrounding residual traffic fused in
 // (the "dropout, residual, LayerNorm" group of Sec. 4.1.1, dropout-free; RMSNorm per Sec. 5.4).
-// HBM-bound: one wave owns a whole row in registers, every access is a 16-byte chunk and a wave's
-// 64 lanes cover 1 KiB contiguous bytes per instruction.  Statistics are fp32; a wave reduction
-// gives the row sums.
+// HBM-bound: every access is a 16-byte chunk and a wave's 64 lanes cover 1 KiB contiguous bytes per
+// instruction.  Statistics are fp32; wave reductions combined through LDS give the row sums.
 #include "norm.h"
 #include "common.h"
 
 namespace {
-
-constexpr int MAXC = 16;   // 16-byte chunks per lane: hidden <= 8 * 64 * 16 = 8192
 
 DEV void unpack8(const u32x4 v, float* f) {
   f[0] = bf16_lo(v[0]); f[1] = bf16_hi(v[0]); f[2] = bf16_lo(v[1]); f[3] = bf16_hi(v[1]);
@@ -21,14 +18,17 @@ DEV u32x4 pack8(const float* f) {
 
 // y = Norm(x + add1 + add2 + vec) * gamma + beta; optionally writes the pre-norm sum (bf16) too.
 // The statistics are taken from the bf16-rounded sum, i.e. from exactly what the backward re-reads.
-// Every load of a phase is issued before the first is used (chunks past the row end read the last chunk
-// instead of branching, and are masked out of the sums and stores): a wave has 10-40 loads in flight.
+// A workgroup of four waves owns one row, thread t the 16-byte chunks t, t+256, ... (at most 4: hidden <= 8192);
+// every load of a phase is issued before the first is used (chunks past the row end read the last chunk instead
+// of branching, and are masked out of the sums and stores); the two row sums cross the waves through LDS in wave
+// order.  Under 96 registers a lane: such waves fit beside the two 192-register waves that a 256x256 product
+// tile keeps on every SIMD.
 template <int NC, bool RMS>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(256, 5)
 void norm_fwd_kernel(const NormFwdArgs p) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= p.rows) return;
+  __shared__ float red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.x;
   const int nch = p.h >> 3;
   const long ro = (long)row * p.h;
   const u32x4* x = reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.x) + ro);
@@ -36,12 +36,13 @@ void norm_fwd_kernel(const NormFwdArgs p) {
   const u32x4* a2 = p.add2 ? reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.add2) + ro) : nullptr;
   const u32x4* vec = reinterpret_cast<const u32x4*>(p.vec);
   const bool fused = a1 || a2 || vec;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
 
-  int cc[NC];                                   // chunk index, clamped into the row
+  int cc[NC];
   bool live[NC];
 #pragma unroll
   for (int i = 0; i < NC; ++i) {
-    const int c = lane + 64 * i;
+    const int c = tid + 256 * i;
     live[i] = c < nch;
     cc[i] = live[i] ? c : nch - 1;
   }
@@ -50,7 +51,6 @@ void norm_fwd_kernel(const NormFwdArgs p) {
   for (int i = 0; i < NC; ++i) xs[i] = x[cc[i]];
   if (fused) {
     u32x4 t1[NC], t2[NC], t3[NC];
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int i = 0; i < NC; ++i) t1[i] = a1 ? a1[cc[i]] : zero4;
 #pragma unroll
@@ -79,7 +79,6 @@ void norm_fwd_kernel(const NormFwdArgs p) {
         if (live[i]) o[cc[i]] = xs[i];
     }
   }
-  // gain and shift for the last phase: in flight during the reductions
   const u32x4* gam = reinterpret_cast<const u32x4*>(p.gamma);
   const u32x4* bet = reinterpret_cast<const u32x4*>(p.beta);
   u32x4 gs[NC], bs[NC];
@@ -102,7 +101,10 @@ void norm_fwd_kernel(const NormFwdArgs p) {
       for (int e = 0; e < 8; ++e) t += f[e];
       s += live[i] ? t : 0.0f;
     }
-    mean = wave_sum(s) * inv_h;
+    s = wave_sum(s);
+    if (lane == 0) red[0][wave] = s;
+    __syncthreads();
+    mean = (((red[0][0] + red[0][1]) + red[0][2]) + red[0][3]) * inv_h;
   }
   float ss = 0.0f;
 #pragma unroll
@@ -113,8 +115,11 @@ void norm_fwd_kernel(const NormFwdArgs p) {
     for (int e = 0; e < 8; ++e) { const float d = f[e] - mean; t += d * d; }
     ss += live[i] ? t : 0.0f;
   }
-  const float rstd = rsqrtf(wave_sum(ss) * inv_h + p.eps);
-  if (lane == 0) {
+  ss = wave_sum(ss);
+  if (lane == 0) red[1][wave] = ss;
+  __syncthreads();
+  const float rstd = rsqrtf((((red[1][0] + red[1][1]) + red[1][2]) + red[1][3]) * inv_h + p.eps);
+  if (tid == 0) {
     if (p.mean) p.mean[row] = mean;
     p.rstd[row] = rstd;
   }
@@ -160,37 +165,49 @@ void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
   for (int e = 0; e < 8; ++e) { dg[e] = 0.0f; db[e] = 0.0f; sres[e] = 0.0f; sdx[e] = 0.0f; }
 
   const int r0 = blockIdx.x * rows_per_block, r1 = min(p.rows, r0 + rows_per_block);
-  int buf = 0;
-  for (int rb = r0; rb < r1; rb += R, buf ^= 1) {
-    u32x4 xs[R], gs[R], bs[R], ds[R];
-    float mean[R], rstd[R];
+  // the rows of iteration k+1 are requested before iteration k is worked on, so the memory pipeline stays
+  // busy across the barrier and the arithmetic of an iteration
+  struct Rows { u32x4 xs[R], gs[R], bs[R], ds[R]; float mean[R], rstd[R]; };
+  auto load_rows = [&](int rb, Rows& w) {
 #pragma unroll
     for (int j = 0; j < R; ++j) {
       const int row = rb + j;
       const bool ok = live && row < r1;
       const long at = (long)row * p.h + tid * 8;
-      xs[j] = ok ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.x) + at) : zero4;
-      gs[j] = ok ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.ga) + at) : zero4;
-      bs[j] = (ok && p.gb) ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.gb) + at) : zero4;
-      ds[j] = (ok && p.dres) ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.dres) + at) : zero4;
-      mean[j] = (!RMS && row < r1) ? p.mean[row] : 0.0f;
-      rstd[j] = row < r1 ? p.rstd[row] : 0.0f;
+      w.xs[j] = ok ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.x) + at) : zero4;
+      w.gs[j] = ok ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.ga) + at) : zero4;
+      w.bs[j] = (ok && p.gb) ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.gb) + at) : zero4;
+      w.ds[j] = (ok && p.dres) ? *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.dres) + at) : zero4;
+      w.mean[j] = (!RMS && row < r1) ? p.mean[row] : 0.0f;
+      w.rstd[j] = row < r1 ? p.rstd[row] : 0.0f;
     }
-    float gv[R][8], sums[2 * R];
+  };
+  Rows cur, nxt;
+  load_rows(r0, cur);
+  int buf = 0;
+  for (int rb = r0; rb < r1; rb += R, buf ^= 1) {
+    load_rows(rb + R, nxt);                     // rows past r1 load nothing
+    const u32x4 (&xs)[R] = cur.xs;
+    const u32x4 (&gs)[R] = cur.gs;
+    const u32x4 (&bs)[R] = cur.bs;
+    const u32x4 (&ds)[R] = cur.ds;
+    const float (&mean)[R] = cur.mean;
+    const float (&rstd)[R] = cur.rstd;
+    float sums[2 * R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-      float xv[8], bv[8];
-      unpack8(xs[j], xv); unpack8(gs[j], gv[j]); unpack8(bs[j], bv);
+      float xv[8], gv[8], bv[8];
+      unpack8(xs[j], xv); unpack8(gs[j], gv); unpack8(bs[j], bv);
       float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        gv[j][e] += bv[e];
+        gv[e] += bv[e];
         const float xh = (xv[e] - mean[j]) * rstd[j];
-        const float dxh = gv[j][e] * gm[e];
+        const float dxh = gv[e] * gm[e];
         s1 += dxh;
         s2 += dxh * xh;
-        dg[e] += gv[j][e] * xh;
-        if (!RMS) db[e] += gv[j][e];
+        dg[e] += gv[e] * xh;
+        if (!RMS) db[e] += gv[e];
       }
       sums[2 * j] = RMS ? 0.0f : wave_sum(s1);
       sums[2 * j + 1] = wave_sum(s2);
@@ -216,16 +233,17 @@ void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
       const int row = rb + j;
       if (live && row < r1) {
         const float c1 = tot[2 * j] * inv_h, c2 = tot[2 * j + 1] * inv_h;
-        float o[8], rv[8], xv[8];
-        unpack8(ds[j], rv); unpack8(xs[j], xv);
+        float o[8], rv[8], xv[8], gv[8], bv[8];     // the incoming gradient is unpacked again rather than kept
+        unpack8(ds[j], rv); unpack8(xs[j], xv); unpack8(gs[j], gv); unpack8(bs[j], bv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          o[e] = rstd[j] * (gv[j][e] * gm[e] - c1 - (xv[e] - mean[j]) * rstd[j] * c2) + rv[e];
+          o[e] = rstd[j] * ((gv[e] + bv[e]) * gm[e] - c1 - (xv[e] - mean[j]) * rstd[j] * c2) + rv[e];
           if (SUMS) { sres[e] += rv[e]; sdx[e] += o[e]; }
         }
         *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.dx) + (long)row * p.h + tid * 8) = pack8(o);
       }
     }
+    cur = nxt;
   }
   if (live) {
     f32x4* pg = reinterpret_cast<f32x4*>(p.part_g + (long)blockIdx.x * p.h + tid * 8);
@@ -298,12 +316,12 @@ void colsum_partial_kernel(const bf16_t* __restrict__ g, long ld, int rows, int 
 
 template <bool RMS>
 hipError_t fwd_dispatch(const NormFwdArgs& a, hipStream_t st) {
-  const int nc = ((a.h >> 3) + 63) / 64;
-  dim3 grid((a.rows + 3) / 4), block(256);
-  if (nc <= 4) hipLaunchKernelGGL((norm_fwd_kernel<4, RMS>), grid, block, 0, st, a);
-  else if (nc <= 8) hipLaunchKernelGGL((norm_fwd_kernel<8, RMS>), grid, block, 0, st, a);
-  else if (nc <= 10) hipLaunchKernelGGL((norm_fwd_kernel<10, RMS>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((norm_fwd_kernel<MAXC, RMS>), grid, block, 0, st, a);
+  const int nq = ((a.h >> 3) + 255) / 256;               // 16-byte chunks per thread
+  const dim3 grid(a.rows), block(256);
+  if (nq <= 1) hipLaunchKernelGGL((norm_fwd_kernel<1, RMS>), grid, block, 0, st, a);
+  else if (nq <= 2) hipLaunchKernelGGL((norm_fwd_kernel<2, RMS>), grid, block, 0, st, a);
+  else if (nq <= 3) hipLaunchKernelGGL((norm_fwd_kernel<3, RMS>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((norm_fwd_kernel<4, RMS>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 
@@ -312,11 +330,12 @@ hipError_t bwd_dispatch(const NormBwdArgs& a, int nblocks, hipStream_t st) {
   const int nt = (((a.h >> 3) + 63) / 64) * 64;           // one thread per 16-byte chunk of a row
   const int rpb = (a.rows + nblocks - 1) / nblocks;
   const dim3 grid(nblocks), block(nt);
-  constexpr int RW = SUMS ? 2 : 4;                        // rows per iteration where registers are tight
-  if (nt <= 256) hipLaunchKernelGGL((norm_bwd_kernel<256, 4, RMS, SUMS>), grid, block, 0, st, a, rpb);
-  else if (nt <= 512) hipLaunchKernelGGL((norm_bwd_kernel<512, 4, RMS, SUMS>), grid, block, 0, st, a, rpb);
-  else if (nt <= 768) hipLaunchKernelGGL((norm_bwd_kernel<768, RW, RMS, SUMS>), grid, block, 0, st, a, rpb);
-  else hipLaunchKernelGGL((norm_bwd_kernel<1024, 2, RMS, SUMS>), grid, block, 0, st, a, rpb);
+  // rows per iteration: two iterations' loads are held at once, within the registers the block size leaves
+  constexpr int RS = SUMS ? 2 : 4;
+  if (nt <= 256) hipLaunchKernelGGL((norm_bwd_kernel<256, RS, RMS, SUMS>), grid, block, 0, st, a, rpb);
+  else if (nt <= 512) hipLaunchKernelGGL((norm_bwd_kernel<512, RS, RMS, SUMS>), grid, block, 0, st, a, rpb);
+  else if (nt <= 768) hipLaunchKernelGGL((norm_bwd_kernel<768, 2, RMS, SUMS>), grid, block, 0, st, a, rpb);
+  else hipLaunchKernelGGL((norm_bwd_kernel<1024, 1, RMS, SUMS>), grid, block, 0, st, a, rpb);
   return hipGetLastError();
 }
 
