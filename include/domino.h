@@ -16,7 +16,11 @@
  *     return, everything is ordered before later work submitted to streams[0].  No host sync.
  *   - Return value: DOMINO_OK or a negative DOMINO_ERR_*; domino_last_error() gives the text.
  *     Arguments are validated before any GPU call, so invalid calls fail the same way on a host
- *     without a GPU.  The library never throws and never aborts.
+ *     without a GPU.  The library never throws and never aborts.  DOMINO_ERR_HIP can come back in the
+ *     middle of a call's launches: the streams may then hold part of the work, not joined to streams[0];
+ *     synchronise the device before using the buffers or the pool again.
+ *   - All streams of a call belong to the current device.  Calls are serialised by a lock inside the
+ *     library; the events for the edges between streams are cached per device (domino_shutdown frees them).
  *   - Every single tensor must be smaller than 2 GiB (32-bit buffer offsets in the kernels).
  */
 #ifndef DOMINO_H

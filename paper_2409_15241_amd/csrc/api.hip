@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <mutex>
 #include <vector>
 
@@ -133,16 +134,27 @@ int validate(const domino_cfg* c, Layout* L) {
 
 // ---------------------------------------------------------------------------------- events, profiling
 std::mutex g_mutex;
-std::vector<hipEvent_t> g_sync_events;     // timing disabled, for cross-stream edges
-size_t g_sync_used = 0;
+// Events for the cross-stream edges of a call (timing disabled), kept per device and handed out again from the
+// first by the next call on that device: an edge already enqueued keeps the record it was made with.
+struct EventPool { std::vector<hipEvent_t> events; size_t used = 0; };
+std::map<int, EventPool> g_pools;
+EventPool* g_pool = nullptr;               // the current device's pool, set by begin_call()
+
+int begin_call() {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+  g_pool = &g_pools[dev];
+  g_pool->used = 0;
+  return DOMINO_OK;
+}
 
 int next_sync_event(hipEvent_t* ev) {
-  if (g_sync_used == g_sync_events.size()) {
+  if (g_pool->used == g_pool->events.size()) {
     hipEvent_t e;
     HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming), "hipEventCreate");
-    g_sync_events.push_back(e);
+    g_pool->events.push_back(e);
   }
-  *ev = g_sync_events[g_sync_used++];
+  *ev = g_pool->events[g_pool->used++];
   return DOMINO_OK;
 }
 
@@ -640,7 +652,7 @@ int domino_layer_fwd_parts(const domino_cfg* cfg, const domino_params* P,
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
-  g_sync_used = 0;
+  TRY(begin_call());
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   const StreamPlan S(streams, nstreams, L.p, L.q);
@@ -678,7 +690,7 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
-  g_sync_used = 0;
+  TRY(begin_call());
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   B.red = reinterpret_cast<float*>(at(workspace, L.red));
@@ -720,7 +732,7 @@ int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < need) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
   std::lock_guard<std::mutex> lock(g_mutex);
-  g_sync_used = 0;
+  TRY(begin_call());
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   // a row slice of block l+1 needs only the same row slice of block l (Sec. 3.2): the slices run through the
@@ -758,7 +770,7 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   }
   TRY(check_streams(streams, nstreams));
   std::lock_guard<std::mutex> lock(g_mutex);
-  g_sync_used = 0;
+  TRY(begin_call());
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   const StreamPlan S(streams, nstreams, L.p, 1);
@@ -934,9 +946,10 @@ int domino_profile_reset(void) {
 
 void domino_shutdown(void) {
   std::lock_guard<std::mutex> lock(g_mutex);
-  for (auto e : g_sync_events) (void)hipEventDestroy(e);
-  g_sync_events.clear();
-  g_sync_used = 0;
+  for (auto& kv : g_pools)
+    for (auto e : kv.second.events) (void)hipEventDestroy(e);
+  g_pools.clear();
+  g_pool = nullptr;
   for (auto& r : g_prof_recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
   g_prof_recs.clear();
   for (auto e : g_prof_free) (void)hipEventDestroy(e);
