@@ -51,11 +51,21 @@ DEV float gelu_grad_f(float x, bool tanh_form) {
 }
 DEV float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
 
-// wave64 reductions over all lanes
+// wave64 reductions over all lanes, on the VALU's data-parallel primitives (no LDS traffic): swaps inside quads,
+// rotations inside the rows of 16 lanes, then the two row broadcasts leave the total in lane 63, which is read
+// back as a wave-uniform value.  The order of the additions is fixed.
+template <int CTRL, int ROW_MASK>
+DEV float dpp_take(float v) {    // lanes of the rows in ROW_MASK get the CTRL-selected lane's v, all others 0
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
 DEV float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_take<0xB1, 0xF>(v);     // quad_perm [1,0,3,2]
+  v += dpp_take<0x4E, 0xF>(v);     // quad_perm [2,3,0,1]
+  v += dpp_take<0x124, 0xF>(v);    // row_ror:4
+  v += dpp_take<0x128, 0xF>(v);    // row_ror:8: every lane holds its row's sum
+  v += dpp_take<0x142, 0xA>(v);    // row_bcast:15 into rows 1 and 3
+  v += dpp_take<0x143, 0xC>(v);    // row_bcast:31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 DEV float wave_max(float v) {
 #pragma unroll
