@@ -23,6 +23,11 @@
 
 namespace {
 
+// 2^x as the bare hardware instruction: the arguments here are differences to a running maximum or to the
+// log-sum-exp (at most about 0; -inf for masked scores gives 0), where results below 2^-126 may flush to zero,
+// so the range fix-up that the library's exp2f wraps around it (a compare, two selects and an ldexp per value)
+// is dead weight on the vector ALUs that bound these kernels.
+DEV float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -204,7 +209,7 @@ void attn_fwd_kernel(const AttnArgs p) {
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;       // scores scaled to the log2 domain (sc > 0)
     const float m_new = fmaxf(m, mx);                  // finite: key 0 is visible to every query
     if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {   // rescale only when some query's maximum moved
-      const float alpha = exp2f(m - m_new);
+      const float alpha = exp2_raw(m - m_new);
       l *= alpha;
 #pragma unroll
       for (int dt = 0; dt < X::DT; ++dt)
@@ -217,7 +222,7 @@ void attn_fwd_kernel(const AttnArgs p) {
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float e = exp2f(sT[t][v] * sc - m);
+        const float e = exp2_raw(sT[t][v] * sc - m);
         sT[t][v] = e;
         rs += e;
       }
@@ -469,7 +474,7 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        float pr = exp2f(sT[t][v] * sc - lse2);
+        float pr = exp2_raw(sT[t][v] * sc - lse2);
         if (diag && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
         sT[t][v] = pr * (dpT[t][v] - dq_dot);
       }
@@ -565,7 +570,7 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int v = 4 * g + e;
-          float pr = exp2f(sm[t][v] * sc - lf[e] * LOG2E);
+          float pr = exp2_raw(sm[t][v] * sc - lf[e] * LOG2E);
           if (diag && q0 + 32 * t + 8 * g + 4 * fh + e < kpos) pr = 0.0f;
           pm[t][v] = pr;
           sm[t][v] = pr * (dpm[t][v] - df[e]);
