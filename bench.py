@@ -101,8 +101,8 @@ def cpu_baseline(sc, budget_s=30.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--streams", type=int, default=4)
     ap.add_argument("--layers", type=int, default=1,
@@ -185,6 +185,16 @@ def main():
         e1.record(s0)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
+    # the step again, one event pair per step on streams[0]: spread of the single steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for e0, e1 in evs:
+        e0.record(s0)
+        step()
+        e1.record(s0)
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    ms_median, ms_min, ms_max = per_step[len(per_step) // 2], per_step[0], per_step[-1]
     fwd_ms = timed(buf.forward, max(3, args.steps // 3))
     bwd_ms = timed(lambda: buf.backward(False), max(3, args.steps // 3))
 
@@ -296,7 +306,8 @@ def main():
                    "batch": sc.batch, "seq": sc.seq, "ffn": sc.ffn, "p": sc.p, "q": sc.q,
                    "arch": "llama" if sc.arch else "gpt", "streams": args.streams, "layers": args.layers},
         "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
-        "algorithmic_gflop_per_step": flops / 1e9, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "algorithmic_gflop_per_step": flops / 1e9, "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
+        "ms_per_step_max": ms_max, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
         "stack": stack, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -365,8 +365,10 @@ int gemm_pick_tile(int M, int N, int concurrency) {
     double rounds, rate = c.rate;
     if (concurrency >= 3) {
       // a launch of very few tiles is a long serial kernel on its stream's critical path: charge a
-      // tile shape for leaving most of a fair share of the chip (256 / concurrency CUs) unused
-      const double share = 256.0 / concurrency;
+      // tile shape for leaving most of a quarter of its fair share of the chip (256 / concurrency CUs)
+      // unused.  (Charging it against the whole share was measured 0.7 % slower on the 13B shard: the
+      // 640-column input gradient is best served by 24 tiles of 256x256, padding included.)
+      const double share = 64.0 / concurrency;
       rounds = tiles / 256.0 * (tiles < share ? share / tiles : 1.0);
     } else if (c.id == GEMM_TILE_128x128) {
       const double t = tiles * concurrency;
