@@ -1,7 +1,8 @@
 // Host side of the C ABI declared in include/domino.h: argument validation, memory layout of the
-// saved / workspace blocks, the p x q piece schedule over the caller's stream pool, and the
-// single-kernel entry points.  No device memory is allocated here and no host synchronisation is
-// performed by the layer calls.
+// saved / workspace blocks, the p x q piece schedule over the caller's stream pool (one block, one
+// block cut at its all-reduce points, or a stack of blocks whose row slices run on without joining),
+// and the single-kernel entry points.  No device memory is allocated here and no host synchronisation
+// is performed by the layer calls.
 #include "../../include/domino.h"
 
 #include <hip/hip_runtime.h>
