@@ -147,7 +147,7 @@ def test_mid_shapes_with_ragged_tiles(H, sc):
     case(H, sc, random_affine=True)
 
 
-FULL = [synth.WORKLOADS[n] for n in ("gpt3-13b", "llama2-7b", "gpt3-30b", "gpt3-2.7b-s512-mb64")]
+FULL = [synth.WORKLOADS[n] for n in ("gpt3-13b", "llama2-7b", "gpt3-30b", "gpt3-2.7b-s512-mb64", "llama2-13b-s512-mb16")]
 
 
 @pytest.mark.parametrize("sc", FULL, ids=[m.name for m in FULL])

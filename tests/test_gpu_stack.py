@@ -136,9 +136,10 @@ def test_stack_accumulates_and_repeats_bitwise(H):
                 assert float((G1[k] - 2 * g).abs().max()) <= 1e-5 * float(g.abs().max()), k
 
 
-def test_full_size_stack_matches_single_blocks_bitwise(H):
-    """The benchmark's shard (GPT-3 13B, p=4, q=2, 4 streams), two blocks."""
-    sc = synth.WORKLOADS["gpt3-13b"]
+@pytest.mark.parametrize("name", ["gpt3-13b", "llama2-7b"])
+def test_full_size_stack_matches_single_blocks_bitwise(H, name):
+    """The benchmark's shard (GPT-3 13B, p=4, q=2, 4 streams) and a Llama shard (p=2, q=4), two blocks."""
+    sc = synth.WORKLOADS[name]
     params, others = synth.make_stack(sc, 2)
     x, dy = synth.make_activations(sc)
     st = run_stack(H, sc, params, others, x, dy, 4)
