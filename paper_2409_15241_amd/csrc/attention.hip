@@ -368,12 +368,22 @@ DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>
   });
 }
 
-// out[dt] += TileT[32 dt + lane%32, pos] * bf16(vals)[pos, lane]: vals = two accumulators covering the
-// tile's 64 positions; off = rm_trans_off(lane).
-template <int D>
-DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const f32x16 (&vals)[2], f32x16 (&out)[Dims<D>::DT]) {
-  using X = Dims<D>;
-  bf16x8 pf[4];
+// acc += a * b with acc pinned to the accumulation registers
+DEV void mfma_keep(const bf16x8 a, const bf16x8 b, f32x16& acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// states that the running sums sit in the accumulation registers at this point (keeps them there across the
+// loop's back edge)
+template <int N>
+DEV void pin_acc(f32x16 (&acc)[N]) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+a"(acc[i]));
+}
+
+// Two accumulators covering a tile's 64 positions, rounded to bf16 as the second operand of rm_mma_cols:
+// fragment s4 = 2 t + u holds accumulator t's values 8 u .. 8 u + 7.
+DEV void pack_acc_pair(const f32x16 (&vals)[2], bf16x8 (&pf)[4]) {
 #pragma unroll
   for (int s4 = 0; s4 < 4; ++s4) {
     const int t = s4 >> 1, u = s4 & 1;
@@ -381,6 +391,13 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const f32x16 (&vals)[2], 
                pack_bf16(vals[t][8 * u + 4], vals[t][8 * u + 5]), pack_bf16(vals[t][8 * u + 6], vals[t][8 * u + 7])};
     pf[s4] = __builtin_bit_cast(bf16x8, w);
   }
+}
+
+// out[dt] += TileT[32 dt + lane%32, pos] * pf[pos, lane]: pf = packed values covering the tile's 64
+// positions (see pack_acc_pair); off = rm_trans_off(lane).
+template <int D>
+DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const bf16x8 (&pf)[4], f32x16 (&out)[Dims<D>::DT]) {
+  using X = Dims<D>;
   u32x2 vf[2][4][2];
   auto read_v = [&](auto dd) {
     constexpr int DTI = decltype(dd)::value;
@@ -401,10 +418,15 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const f32x16 (&vals)[2], 
       tie(vf[DTI & 1][s4][0]);
       tie(vf[DTI & 1][s4][1]);
       const u32x4 a = {vf[DTI & 1][s4][0][0], vf[DTI & 1][s4][0][1], vf[DTI & 1][s4][1][0], vf[DTI & 1][s4][1][1]};
-      out[DTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI], 0, 0, 0);
+      // the running sums stay in the accumulation registers for the whole pass: written as asm so that the
+      // register allocator cannot move them to the vector registers and back around every tile
+      mfma_keep(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI]);
     }
   });
 }
+// Before the sums of rm_mma_cols are read by ordinary vector instructions the last MFMA must have left the
+// matrix pipe (8 passes); the compiler cannot see that dependency through the asm statement.
+DEV void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 
 constexpr int RM_TILE = 16384;
 
@@ -456,6 +478,7 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
 
   issue_tile(0);
   for (int j = 0; j < ntiles; ++j) {
+    pin_acc(dq);
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     if (j + 1 < ntiles) issue_tile(j + 1);
@@ -478,8 +501,11 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
         if (diag && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
         sT[t][v] = pr * (dpT[t][v] - dq_dot);
       }
-    rm_mma_cols<D>(st, offT, sT, dq);                    // dQ^T += K^T dS^T
+    bf16x8 dsf[4];
+    pack_acc_pair(sT, dsf);
+    rm_mma_cols<D>(st, offT, dsf, dq);                   // dQ^T += K^T dS^T
   }
+  mfma_drain();
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + qpos) * ld + hh * D;
     store_transposed<D>(dq, p.scale, out, fh);
@@ -536,6 +562,8 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
 
   issue_tile(j0, 0);
   for (int j = j0; j < nq; ++j) {
+    pin_acc(dk);
+    pin_acc(dv);
     const int slot = (j - j0) & 1;
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
@@ -551,7 +579,7 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
     rm_mma_rows<D>(st, offP, kf, sm);                     // S[q, kv]  = Q K^T
     rm_mma_rows<D>(st + RM_TILE, offP, vf, dpm);          // dP[q, kv] = dO V^T
     const bool diag = q0 < kw0 + 31;
-    f32x16 pm[2];
+    u32x4 pw[4], dw[4];                                   // P and dS rounded to bf16 as they are formed
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       u32x4 l4[4], d4[4];
@@ -567,19 +595,28 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
         tie(l4[g]);
         tie(d4[g]);
         const f32x4 lf = __builtin_bit_cast(f32x4, l4[g]), df = __builtin_bit_cast(f32x4, d4[g]);
+        float pr[4], ds[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int v = 4 * g + e;
-          float pr = exp2_raw(sm[t][v] * sc - lf[e] * LOG2E);
-          if (diag && q0 + 32 * t + 8 * g + 4 * fh + e < kpos) pr = 0.0f;
-          pm[t][v] = pr;
-          sm[t][v] = pr * (dpm[t][v] - df[e]);
+          pr[e] = exp2_raw(sm[t][v] * sc - lf[e] * LOG2E);
+          if (diag && q0 + 32 * t + 8 * g + 4 * fh + e < kpos) pr[e] = 0.0f;
+          ds[e] = pr[e] * (dpm[t][v] - df[e]);
         }
+        // values 4 g .. 4 g + 3 of accumulator t are words 2 (g & 1), 2 (g & 1) + 1 of fragment 2 t + (g >> 1)
+        pw[2 * t + (g >> 1)][2 * (g & 1)] = pack_bf16(pr[0], pr[1]);
+        pw[2 * t + (g >> 1)][2 * (g & 1) + 1] = pack_bf16(pr[2], pr[3]);
+        dw[2 * t + (g >> 1)][2 * (g & 1)] = pack_bf16(ds[0], ds[1]);
+        dw[2 * t + (g >> 1)][2 * (g & 1) + 1] = pack_bf16(ds[2], ds[3]);
       }
     }
-    rm_mma_cols<D>(st + RM_TILE, offT, pm, dv);           // dV^T += dO^T P
-    rm_mma_cols<D>(st, offT, sm, dk);                     // dK^T += Q^T dS
+    bf16x8 pf[4], dsf[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) { pf[s4] = __builtin_bit_cast(bf16x8, pw[s4]); dsf[s4] = __builtin_bit_cast(bf16x8, dw[s4]); }
+    rm_mma_cols<D>(st + RM_TILE, offT, pf, dv);           // dV^T += dO^T P
+    rm_mma_cols<D>(st, offT, dsf, dk);                    // dK^T += Q^T dS
   }
+  mfma_drain();
   if (kpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + kpos) * ld + hh * D;
     store_transposed<D>(dk, p.scale, out + hl, fh);
