@@ -423,10 +423,21 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const bf16x8 (&pf)[4], f3
       mfma_keep(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI]);
     }
   });
+  // An MFMA reads its operand registers pass by pass while it runs (8 passes of 4 clocks).  For the built-in
+  // MFMAs the compiler keeps later writers of those registers away; for the asm ones it cannot, and the fragment
+  // reads of whatever follows would land in `vf` under the last MFMA (seen as wrong last rows of its tile).
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(out[X::DT - 1]));
 }
 // Before the sums of rm_mma_cols are read by ordinary vector instructions the last MFMA must have left the
-// matrix pipe (8 passes); the compiler cannot see that dependency through the asm statement.
-DEV void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+// matrix pipe (8 passes of 4 clocks, behind the MFMAs queued before it); the compiler cannot see that
+// dependency through the asm statements, so the wait is written out and tied to the registers: every later
+// read of the sums depends on one of these statements, and they keep their order after the MFMAs.
+template <int N>
+DEV void mfma_drain(f32x16 (&acc)[N]) {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(acc[N - 1]));
+#pragma unroll
+  for (int i = 0; i < N - 1; ++i) asm volatile("" : "+a"(acc[i]));
+}
 
 constexpr int RM_TILE = 16384;
 
@@ -492,20 +503,22 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
       for (int v = 0; v < 16; ++v) { sT[t][v] = 0.0f; dpT[t][v] = 0.0f; }
     rm_mma_rows<D>(st, offP, qf, sT);                    // S^T  = K Q^T
     rm_mma_rows<D>(st + RM_TILE, offP, dof, dpT);        // dP^T = V dO^T
-    const bool diag = kv0 + 63 > qw0;
+    auto probs = [&](auto masked) {                       // the mask arithmetic only where the tile meets the diagonal
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float pr = exp2_raw(sT[t][v] * sc - lse2);
-        if (diag && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
-        sT[t][v] = pr * (dpT[t][v] - dq_dot);
-      }
+        for (int v = 0; v < 16; ++v) {
+          float pr = exp2_raw(sT[t][v] * sc - lse2);
+          if (decltype(masked)::value && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
+          sT[t][v] = pr * (dpT[t][v] - dq_dot);
+        }
+    };
+    if (kv0 + 63 > qw0) probs(std::true_type{}); else probs(std::false_type{});
     bf16x8 dsf[4];
     pack_acc_pair(sT, dsf);
     rm_mma_cols<D>(st, offT, dsf, dq);                   // dQ^T += K^T dS^T
   }
-  mfma_drain();
+  mfma_drain(dq);
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + qpos) * ld + hh * D;
     store_transposed<D>(dq, p.scale, out, fh);
@@ -578,8 +591,8 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
       for (int v = 0; v < 16; ++v) { sm[t][v] = 0.0f; dpm[t][v] = 0.0f; }
     rm_mma_rows<D>(st, offP, kf, sm);                     // S[q, kv]  = Q K^T
     rm_mma_rows<D>(st + RM_TILE, offP, vf, dpm);          // dP[q, kv] = dO V^T
-    const bool diag = q0 < kw0 + 31;
     u32x4 pw[4], dw[4];                                   // P and dS rounded to bf16 as they are formed
+    auto probs = [&](auto masked) {                       // the mask arithmetic only where the tile meets the diagonal
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       u32x4 l4[4], d4[4];
@@ -600,7 +613,7 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
         for (int e = 0; e < 4; ++e) {
           const int v = 4 * g + e;
           pr[e] = exp2_raw(sm[t][v] * sc - lf[e] * LOG2E);
-          if (diag && q0 + 32 * t + 8 * g + 4 * fh + e < kpos) pr[e] = 0.0f;
+          if (decltype(masked)::value && q0 + 32 * t + 8 * g + 4 * fh + e < kpos) pr[e] = 0.0f;
           ds[e] = pr[e] * (dpm[t][v] - df[e]);
         }
         // values 4 g .. 4 g + 3 of accumulator t are words 2 (g & 1), 2 (g & 1) + 1 of fragment 2 t + (g >> 1)
@@ -610,13 +623,16 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
         dw[2 * t + (g >> 1)][2 * (g & 1) + 1] = pack_bf16(ds[2], ds[3]);
       }
     }
+    };
+    if (q0 < kw0 + 31) probs(std::true_type{}); else probs(std::false_type{});
     bf16x8 pf[4], dsf[4];
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) { pf[s4] = __builtin_bit_cast(bf16x8, pw[s4]); dsf[s4] = __builtin_bit_cast(bf16x8, dw[s4]); }
     rm_mma_cols<D>(st + RM_TILE, offT, pf, dv);           // dV^T += dO^T P
     rm_mma_cols<D>(st, offT, dsf, dk);                    // dK^T += Q^T dS
   }
-  mfma_drain();
+  mfma_drain(dv);
+  mfma_drain(dk);
   if (kpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + kpos) * ld + hh * D;
     store_transposed<D>(dk, p.scale, out + hl, fh);
