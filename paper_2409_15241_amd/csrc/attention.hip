@@ -206,7 +206,7 @@ void attn_fwd_kernel(const AttnArgs p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sT[t][v]);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;       // scores scaled to the log2 domain (sc > 0)
+    mx = fmaxf(mx, other_half(mx)) * sc;       // scores scaled to the log2 domain (sc > 0)
     const float m_new = fmaxf(m, mx);                  // finite: key 0 is visible to every query
     if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {   // rescale only when some query's maximum moved
       const float alpha = exp2_raw(m - m_new);
@@ -261,7 +261,7 @@ void attn_fwd_kernel(const AttnArgs p) {
       }
     });
   }
-  l += __shfl_xor(l, 32, 64);
+  l += other_half(l);
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.ctx) + ((long)bi * s + qpos) * p.ld_ctx + hh * D;
     store_transposed<D>(o, 1.0f / l, out, fh);

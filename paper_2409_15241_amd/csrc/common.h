@@ -67,6 +67,13 @@ DEV float wave_sum(float v) {
   v += dpp_take<0x143, 0xC>(v);    // row_bcast:31 into rows 2 and 3
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
+// value of the lane 32 away (the other half of the wave) through the gfx950 half-swap instruction: no LDS
+// permute and no wait on the LDS counter
+DEV float other_half(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);   // r[0] = [lo, lo], r[1] = [hi, hi]
+  return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
+}
 DEV float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
