@@ -85,9 +85,10 @@ TINYL = synth.WORKLOADS["tiny-llama"]
 
 
 @pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
-@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (1, 4), (2, 4), (4, 1), (4, 2), (4, 4)])
+@pytest.mark.parametrize("p,q", [(1, 1), (2, 1), (1, 2), (2, 2), (1, 4), (2, 4), (4, 1), (4, 2), (4, 4), (8, 1), (8, 2),
+                                 (1, 8)])
 def test_tiny_every_slicing(H, base, p, q):
-    sc = base.replace(p=p, q=q, batch=4 if p == 4 else base.batch)
+    sc = base.replace(p=p, q=q, batch=p if p >= 4 else base.batch)
     case(H, sc, random_affine=True)
 
 
