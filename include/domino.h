@@ -245,7 +245,8 @@ int domino_attention_bwd(const void* qkv, int64_t ld, const void* ctx, const voi
 
 /* Rotary embedding in place on nblocks consecutive [heads*head_dim]-wide column blocks of
  * m[rows, ld] starting at column col0 (pairs (i, i + d/2), angle pos * base^(-2i/d), pos = row % seq);
- * inverse != 0 applies the transposed rotation. */
+ * inverse != 0 applies the transposed rotation.  head_dim must be a multiple of 16, col0 and ld multiples of 8
+ * (16-byte accesses). */
 int domino_rope(void* m, int64_t ld, int rows, int seq, int col0, int nblocks, int heads, int head_dim,
                 float base, int inverse, void* stream);
 

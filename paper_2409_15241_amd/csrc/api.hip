@@ -892,8 +892,9 @@ int domino_attention_bwd(const void* qkv, int64_t ld, const void* ctx, const voi
 int domino_rope(void* m, int64_t ld, int rows, int seq, int col0, int nblocks, int heads, int head_dim,
                 float base, int inverse, void* stream) {
   if (!m) return fail(DOMINO_ERR_NULL_POINTER, "m is NULL");
-  if (rows <= 0 || seq <= 0 || nblocks <= 0 || heads <= 0 || head_dim <= 0 || head_dim % 2 || col0 < 0)
-    return fail(DOMINO_ERR_INVALID_ARG, "rows, seq, nblocks, heads must be positive and head_dim even");
+  if (rows <= 0 || seq <= 0 || nblocks <= 0 || heads <= 0 || head_dim <= 0 || col0 < 0)
+    return fail(DOMINO_ERR_INVALID_ARG, "rows, seq, nblocks, heads, head_dim must be positive");
+  if (head_dim % 16 || col0 % 8 || ld % 8) return fail(DOMINO_ERR_UNSUPPORTED, "head_dim must be a multiple of 16, col0 and ld multiples of 8");
   if (col0 + (long)nblocks * heads * head_dim > ld) return fail(DOMINO_ERR_INVALID_ARG, "column blocks exceed ld");
   if (!(base > 1.0f)) return fail(DOMINO_ERR_INVALID_ARG, "base must exceed 1");
   HIP_TRY(rope_launch(m, ld, rows, seq, col0, nblocks, heads, head_dim, base, inverse, as_stream(stream)), "rope launch");

@@ -4,27 +4,39 @@
 
 namespace {
 
-// One thread per (row, pair index i < d/2): the angle pos * base^(-2i/d) is computed once and the
-// rotation applied to the pair (i, i + d/2) of every head of every column block.
+// One thread per (row, group of 8 pair indices i < d/2): the 8 angles pos * base^(-2i/d) are computed once and
+// the rotation applied to the pairs (i, i + d/2) of every head of every column block with 16-byte accesses.
+// The head dimension is a multiple of 16 here (64, 80, 128), so a group never straddles the half.
 __global__ __launch_bounds__(256)
 void rope_kernel(bf16_t* __restrict__ m, long ld, int rows, int seq, int col0, int nblocks, int heads, int d,
                  float log2_base, int inverse) {
-  const int half = d >> 1;
+  const int half = d >> 1, groups = half >> 3;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (long)rows * half) return;
-  const int row = (int)(idx / half), i = (int)(idx % half);
+  if (idx >= (long)rows * groups) return;
+  const int row = (int)(idx / groups), i0 = (int)(idx % groups) * 8;
   const float pos = (float)(row % seq);
-  const float freq = exp2f(-2.0f * (float)i / (float)d * log2_base);
-  float sn, cs;
-  sincosf(pos * freq, &sn, &cs);
-  if (inverse) sn = -sn;
-  bf16_t* r = m + (long)row * ld + col0;
+  float sn[8], cs[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float freq = exp2f(-2.0f * (float)(i0 + e) / (float)d * log2_base);
+    sincosf(pos * freq, &sn[e], &cs[e]);
+    if (inverse) sn[e] = -sn[e];
+  }
+  bf16_t* r = m + (long)row * ld + col0 + i0;
   for (int blk = 0; blk < nblocks; ++blk)
     for (int hh = 0; hh < heads; ++hh) {
-      bf16_t* p = r + (blk * heads + hh) * d + i;
-      const float a = (float)p[0], b = (float)p[half];
-      p[0] = (bf16_t)(a * cs - b * sn);
-      p[half] = (bf16_t)(b * cs + a * sn);
+      u32x4* plo = reinterpret_cast<u32x4*>(r + (blk * heads + hh) * d);
+      u32x4* phi = reinterpret_cast<u32x4*>(r + (blk * heads + hh) * d + half);
+      const u32x4 lo = *plo, hi = *phi;
+      u32x4 olo, ohi;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float a0 = bf16_lo(lo[w]), a1 = bf16_hi(lo[w]), b0 = bf16_lo(hi[w]), b1 = bf16_hi(hi[w]);
+        olo[w] = pack_bf16(a0 * cs[2 * w] - b0 * sn[2 * w], a1 * cs[2 * w + 1] - b1 * sn[2 * w + 1]);
+        ohi[w] = pack_bf16(b0 * cs[2 * w] + a0 * sn[2 * w], b1 * cs[2 * w + 1] + a1 * sn[2 * w + 1]);
+      }
+      *plo = olo;
+      *phi = ohi;
     }
 }
 
@@ -53,7 +65,7 @@ void residual_out_kernel(const u32x4* __restrict__ x1, const u32x4* __restrict__
 
 hipError_t rope_launch(void* m, long ld, int rows, int seq, int col0, int nblocks, int heads, int d,
                        float base, int inverse, hipStream_t st) {
-  const long n = (long)rows * (d / 2);
+  const long n = (long)rows * (d / 16);
   hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                      static_cast<bf16_t*>(m), ld, rows, seq, col0, nblocks, heads, d, log2f(base), inverse);
   return hipGetLastError();
