@@ -423,10 +423,12 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const bf16x8 (&pf)[4], f3
       mfma_keep(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI]);
     }
   });
-  // An MFMA reads its operand registers pass by pass while it runs (8 passes of 4 clocks).  For the built-in
+  // An MFMA reads its operand registers pass by pass while it runs (8 passes of 4 clocks), and the four MFMAs
+  // of a chain on one accumulator run one after the other however early they were issued.  For the built-in
   // MFMAs the compiler keeps later writers of those registers away; for the asm ones it cannot, and the fragment
-  // reads of whatever follows would land in `vf` under the last MFMA (seen as wrong last rows of its tile).
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(out[X::DT - 1]));
+  // reads of whatever follows landed in `vf` under the last MFMA (seen as wrong last rows of its tile).  Wait
+  // out a whole chain: 4 x 32 clocks.
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(out[X::DT - 1]));
 }
 // Before the sums of rm_mma_cols are read by ordinary vector instructions the last MFMA must have left the
 // matrix pipe (8 passes of 4 clocks, behind the MFMAs queued before it); the compiler cannot see that
@@ -434,7 +436,7 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const bf16x8 (&pf)[4], f3
 // read of the sums depends on one of these statements, and they keep their order after the MFMAs.
 template <int N>
 DEV void mfma_drain(f32x16 (&acc)[N]) {
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(acc[N - 1]));
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(acc[N - 1]));
 #pragma unroll
   for (int i = 0; i < N - 1; ++i) asm volatile("" : "+a"(acc[i]));
 }
