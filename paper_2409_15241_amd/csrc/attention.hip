@@ -368,13 +368,9 @@ DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>
   });
 }
 
-// acc += a * b with acc pinned to the accumulation registers
-DEV void mfma_keep(const bf16x8 a, const bf16x8 b, f32x16& acc) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-
-// states that the running sums sit in the accumulation registers at this point (keeps them there across the
-// loop's back edge)
+// States that the running sums sit in the accumulation registers at this point.  Placed at the top of a pass's
+// loop it keeps them there across the back edge; without it the register allocator carried all of them in
+// vector registers at the loop head and copied them to the accumulation registers and back around every tile.
 template <int N>
 DEV void pin_acc(f32x16 (&acc)[N]) {
 #pragma unroll
@@ -418,27 +414,9 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const bf16x8 (&pf)[4], f3
       tie(vf[DTI & 1][s4][0]);
       tie(vf[DTI & 1][s4][1]);
       const u32x4 a = {vf[DTI & 1][s4][0][0], vf[DTI & 1][s4][0][1], vf[DTI & 1][s4][1][0], vf[DTI & 1][s4][1][1]};
-      // the running sums stay in the accumulation registers for the whole pass: written as asm so that the
-      // register allocator cannot move them to the vector registers and back around every tile
-      mfma_keep(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI]);
+      out[DTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI], 0, 0, 0);
     }
   });
-  // An MFMA reads its operand registers pass by pass while it runs (8 passes of 4 clocks), and the four MFMAs
-  // of a chain on one accumulator run one after the other however early they were issued.  For the built-in
-  // MFMAs the compiler keeps later writers of those registers away; for the asm ones it cannot, and the fragment
-  // reads of whatever follows landed in `vf` under the last MFMA (seen as wrong last rows of its tile).  Wait
-  // out a whole chain: 4 x 32 clocks.
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(out[X::DT - 1]));
-}
-// Before the sums of rm_mma_cols are read by ordinary vector instructions the last MFMA must have left the
-// matrix pipe (8 passes of 4 clocks, behind the MFMAs queued before it); the compiler cannot see that
-// dependency through the asm statements, so the wait is written out and tied to the registers: every later
-// read of the sums depends on one of these statements, and they keep their order after the MFMAs.
-template <int N>
-DEV void mfma_drain(f32x16 (&acc)[N]) {
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(acc[N - 1]));
-#pragma unroll
-  for (int i = 0; i < N - 1; ++i) asm volatile("" : "+a"(acc[i]));
 }
 
 constexpr int RM_TILE = 16384;
@@ -520,7 +498,6 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
     pack_acc_pair(sT, dsf);
     rm_mma_cols<D>(st, offT, dsf, dq);                   // dQ^T += K^T dS^T
   }
-  mfma_drain(dq);
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + qpos) * ld + hh * D;
     store_transposed<D>(dq, p.scale, out, fh);
@@ -633,8 +610,6 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
     rm_mma_cols<D>(st + RM_TILE, offT, pf, dv);           // dV^T += dO^T P
     rm_mma_cols<D>(st, offT, dsf, dk);                    // dK^T += Q^T dS
   }
-  mfma_drain(dv);
-  mfma_drain(dk);
   if (kpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + kpos) * ld + hh * D;
     store_transposed<D>(dk, p.scale, out + hl, fh);
