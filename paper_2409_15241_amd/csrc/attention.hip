@@ -329,11 +329,20 @@ DEV uint32_t rm_trans_off(int lane) {
   return (uint32_t)(posl * 256 + (h << 4) + 8 * (sl & 1));
 }
 
+// Vector-ALU work handed to the MFMA helpers below is issued between their MFMAs: a wave's MFMA occupies the
+// matrix pipe for 32 clocks during which the wave may issue independent vector instructions, but only if they
+// follow that MFMA in program order; a scheduling barrier after each slot keeps the compiler from regrouping them.
+struct NoFill {
+  template <class I> DEV void operator()(I) const {}
+};
+
 // acc[t] += Tile[32 t + lane%32, d] * frag[d, lane] over all d, batches of 4 steps with the next batch's
 // reads in flight.  tile_addr = LDS byte address of the row-major tile, off = rm_plain_off(lane).
-template <int D>
-DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>::KSTEPS], f32x16 (&acc)[2]) {
+// fill(integral_constant<int, ks>) runs after the two MFMAs of step ks.
+template <int D, class F>
+DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>::KSTEPS], f32x16 (&acc)[2], F&& fill) {
   using X = Dims<D>;
+  constexpr bool FILL = !std::is_same<std::decay_t<F>, NoFill>::value;
   constexpr int NB = (X::KSTEPS + 3) / 4;
   u32x4 fr[2][4][2];
   auto read_batch = [&](auto bb) {
@@ -363,6 +372,10 @@ DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>
         for (int t = 0; t < 2; ++t)
           acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[B & 1][decltype(kk)::value][t]),
                                                           f[KS], acc[t], 0, 0, 0);
+        if constexpr (FILL) {
+          fill(std::integral_constant<int, KS>{});
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     });
   });
@@ -416,6 +429,45 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const bf16x8 (&pf)[4], f3
       const u32x4 a = {vf[DTI & 1][s4][0][0], vf[DTI & 1][s4][0][1], vf[DTI & 1][s4][1][0], vf[DTI & 1][s4][1][1]};
       out[DTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pf[s4], out[DTI], 0, 0, 0);
     }
+  });
+}
+
+// The same product taken one 16-position fragment at a time, for a second operand that is still being formed:
+// make(integral_constant<int, s4>, integral_constant<int, lo>, integral_constant<int, hi>) must write words
+// lo .. hi - 1 of pw[s4]; fragment 0 is made up front, fragment s4 + 1 in pieces between the MFMAs of fragment s4.
+template <int D, class F>
+DEV void rm_mma_cols_making(uint32_t tile_addr, uint32_t off, u32x4 (&pw)[4], f32x16 (&out)[Dims<D>::DT], F&& make) {
+  using X = Dims<D>;
+  constexpr int DT = X::DT;
+  u32x2 vf[2][DT][2];
+  auto read_v = [&](auto ss) {
+    constexpr int S4 = decltype(ss)::value;
+    constexpr int OFF = (S4 >> 1) * 8192 + (S4 & 1) * 4096;
+    static_for<0, DT>([&](auto dd) {
+      constexpr int DTI = decltype(dd)::value;
+      vf[S4 & 1][DTI][0] = ds_read_tr_at<OFF>(tile_addr + (off ^ ((4 * DTI) << 4)));
+      vf[S4 & 1][DTI][1] = ds_read_tr_at<OFF + 2048>(tile_addr + (off ^ (((4 * DTI) ^ 2) << 4)));
+    });
+  };
+  read_v(std::integral_constant<int, 0>{});
+  make(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
+  static_for<0, 4>([&](auto ss) {
+    constexpr int S4 = decltype(ss)::value;
+    if constexpr (S4 + 1 < 4) read_v(std::integral_constant<int, S4 + 1>{});
+    lds_wait<(S4 + 1 < 4) ? 2 * DT : 0>();
+    const bf16x8 frag = __builtin_bit_cast(bf16x8, pw[S4]);
+    static_for<0, DT>([&](auto dd) {
+      constexpr int DTI = decltype(dd)::value;
+      tie(vf[S4 & 1][DTI][0]);
+      tie(vf[S4 & 1][DTI][1]);
+      const u32x4 a = {vf[S4 & 1][DTI][0][0], vf[S4 & 1][DTI][0][1], vf[S4 & 1][DTI][1][0], vf[S4 & 1][DTI][1][1]};
+      out[DTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), frag, out[DTI], 0, 0, 0);
+      if constexpr (S4 + 1 < 4) {
+        make(std::integral_constant<int, S4 + 1>{}, std::integral_constant<int, (DTI * 4) / DT>{},
+             std::integral_constant<int, ((DTI + 1) * 4) / DT>{});
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
   });
 }
 
@@ -476,27 +528,37 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
     const int kv0 = j * 64;
     if (kv0 > qw0 + 31) continue;
     const uint32_t st = smem_base + (j & 1) * STAGE;
-    f32x16 sT[2], dpT[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { sT[t][v] = 0.0f; dpT[t][v] = 0.0f; }
-    rm_mma_rows<D>(st, offP, qf, sT);                    // S^T  = K Q^T
-    rm_mma_rows<D>(st + RM_TILE, offP, dof, dpT);        // dP^T = V dO^T
-    auto probs = [&](auto masked) {                       // the mask arithmetic only where the tile meets the diagonal
+    // S^T = K Q^T; then dP^T = V dO^T with P^T = exp2(S^T sc - lse) formed between its MFMAs; then
+    // dQ^T += K^T dS^T fragment by fragment, dS^T = P^T (dP^T - D) of the next fragment between the MFMAs.
+    // The mask arithmetic runs only where the tile meets the diagonal.
+    auto tile = [&](auto masked) {
+      constexpr bool MASKED = decltype(masked)::value;
+      f32x16 sT[2], dpT[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
+        for (int v = 0; v < 16; ++v) { sT[t][v] = 0.0f; dpT[t][v] = 0.0f; }
+      rm_mma_rows<D>(st, offP, qf, sT, NoFill{});
+      rm_mma_rows<D>(st + RM_TILE, offP, dof, dpT, [&](auto ks) {
+        constexpr int CH = (32 + X::KSTEPS - 1) / X::KSTEPS, I0 = decltype(ks)::value * CH;
+#pragma unroll
+        for (int i = I0; i < I0 + CH && i < 32; ++i) {
+          const int t = i >> 4, v = i & 15;
           float pr = exp2_raw(sT[t][v] * sc - lse2);
-          if (decltype(masked)::value && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
-          sT[t][v] = pr * (dpT[t][v] - dq_dot);
+          if (MASKED && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
+          sT[t][v] = pr;
         }
+      });
+      u32x4 dw[4];
+      rm_mma_cols_making<D>(st, offT, dw, dq, [&](auto ss, auto lo, auto hi) {
+        constexpr int S4 = decltype(ss)::value, t = S4 >> 1, b = 8 * (S4 & 1);
+#pragma unroll
+        for (int w = decltype(lo)::value; w < decltype(hi)::value; ++w)
+          dw[S4][w] = pack_bf16(sT[t][b + 2 * w] * (dpT[t][b + 2 * w] - dq_dot),
+                                sT[t][b + 2 * w + 1] * (dpT[t][b + 2 * w + 1] - dq_dot));
+      });
     };
-    if (kv0 + 63 > qw0) probs(std::true_type{}); else probs(std::false_type{});
-    bf16x8 dsf[4];
-    pack_acc_pair(sT, dsf);
-    rm_mma_cols<D>(st, offT, dsf, dq);                   // dQ^T += K^T dS^T
+    if (kv0 + 63 > qw0) tile(std::true_type{}); else tile(std::false_type{});
   }
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + qpos) * ld + hh * D;
@@ -568,8 +630,8 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) { sm[t][v] = 0.0f; dpm[t][v] = 0.0f; }
-    rm_mma_rows<D>(st, offP, kf, sm);                     // S[q, kv]  = Q K^T
-    rm_mma_rows<D>(st + RM_TILE, offP, vf, dpm);          // dP[q, kv] = dO V^T
+    rm_mma_rows<D>(st, offP, kf, sm, NoFill{});           // S[q, kv]  = Q K^T
+    rm_mma_rows<D>(st + RM_TILE, offP, vf, dpm, NoFill{}); // dP[q, kv] = dO V^T
     u32x4 pw[4], dw[4];                                   // P and dS rounded to bf16 as they are formed
     auto probs = [&](auto masked) {                       // the mask arithmetic only where the tile meets the diagonal
 #pragma unroll
