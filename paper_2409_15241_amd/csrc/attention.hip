@@ -78,6 +78,24 @@ DEV void static_for(F&& f) {
   }
 }
 
+// Work order.  Workgroups differ in length by the causal mask (2 to 2 s/64 tiles), and the hardware deals
+// consecutive workgroup ids round-robin over the 8 XCDs: with a plain (block, head, batch) grid the workgroups
+// whose block index is a multiple of 8 (the longest of every head) all land on one XCD, which then carries
+// 2.4 times the work of the last one.  So the launch is a 1-D grid and the work items are ranked instead: rank
+// = (position of the item inside its (batch, head) group, longest first) * groups + group, dealt over the XCDs
+// in snake order (0..7, 7..0, ...): every XCD gets the same mix, longest items first.  Returns the item's
+// position inside its group and the group, or false for the padding workgroups of the last round.
+DEV bool ranked_item(int per_group, int groups, int& pos, int& group) {
+  const int id = __builtin_amdgcn_readfirstlane(blockIdx.x);
+  const int xcd = id & 7, round = id >> 3;
+  const int rank = round * 8 + ((round & 1) ? 7 - xcd : xcd);
+  if (rank >= per_group * groups) return false;
+  pos = rank / groups;
+  group = rank % groups;
+  return true;
+}
+inline int ranked_grid(int per_group, int groups) { return ((per_group * groups + 7) / 8) * 8; }
+
 // One workgroup = 128 queries of one (batch element, head): 4 waves x 32 queries.  K and V tiles of 64
 // keys travel HBM/L2 -> LDS with buffer_load ... lds (double buffered, no VGPR staging): K as
 // contraction-contiguous [kv][32 d] sub-tiles, V as row-major [32 kv][d] sub-tiles read back with the
@@ -95,9 +113,12 @@ void attn_fwd_kernel(const AttnArgs p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x;        // longest rows first
-  const int hh = blockIdx.y, bi = blockIdx.z;
   const int s = p.seq;
+  const int nqb = (s + 127) / 128;
+  int pos, group;
+  if (!ranked_item(nqb, p.heads * p.batch, pos, group)) return;
+  const int qb = nqb - 1 - pos;                     // longest rows first
+  const int hh = group % p.heads, bi = group / p.heads;
   const int qw0 = qb * 128 + wave * 32, qpos = qw0 + fr;
   const long ld = p.ld;
   const bf16_t* tok0 = static_cast<const bf16_t*>(p.qkv) + (long)bi * s * ld;
@@ -329,20 +350,11 @@ DEV uint32_t rm_trans_off(int lane) {
   return (uint32_t)(posl * 256 + (h << 4) + 8 * (sl & 1));
 }
 
-// Vector-ALU work handed to the MFMA helpers below is issued between their MFMAs: a wave's MFMA occupies the
-// matrix pipe for 32 clocks during which the wave may issue independent vector instructions, but only if they
-// follow that MFMA in program order; a scheduling barrier after each slot keeps the compiler from regrouping them.
-struct NoFill {
-  template <class I> DEV void operator()(I) const {}
-};
-
 // acc[t] += Tile[32 t + lane%32, d] * frag[d, lane] over all d, batches of 4 steps with the next batch's
 // reads in flight.  tile_addr = LDS byte address of the row-major tile, off = rm_plain_off(lane).
-// fill(integral_constant<int, ks>) runs after the two MFMAs of step ks.
-template <int D, class F>
-DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>::KSTEPS], f32x16 (&acc)[2], F&& fill) {
+template <int D>
+DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>::KSTEPS], f32x16 (&acc)[2]) {
   using X = Dims<D>;
-  constexpr bool FILL = !std::is_same<std::decay_t<F>, NoFill>::value;
   constexpr int NB = (X::KSTEPS + 3) / 4;
   u32x4 fr[2][4][2];
   auto read_batch = [&](auto bb) {
@@ -372,10 +384,6 @@ DEV void rm_mma_rows(uint32_t tile_addr, uint32_t off, const bf16x8 (&f)[Dims<D>
         for (int t = 0; t < 2; ++t)
           acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[B & 1][decltype(kk)::value][t]),
                                                           f[KS], acc[t], 0, 0, 0);
-        if constexpr (FILL) {
-          fill(std::integral_constant<int, KS>{});
-          __builtin_amdgcn_sched_barrier(0);
-        }
       }
     });
   });
@@ -432,57 +440,16 @@ DEV void rm_mma_cols(uint32_t tile_addr, uint32_t off, const bf16x8 (&pf)[4], f3
   });
 }
 
-// The same product taken one 16-position fragment at a time, for a second operand that is still being formed:
-// make(integral_constant<int, s4>, integral_constant<int, lo>, integral_constant<int, hi>) must write words
-// lo .. hi - 1 of pw[s4]; fragment 0 is made up front, fragment s4 + 1 in pieces between the MFMAs of fragment s4.
-template <int D, class F>
-DEV void rm_mma_cols_making(uint32_t tile_addr, uint32_t off, u32x4 (&pw)[4], f32x16 (&out)[Dims<D>::DT], F&& make) {
-  using X = Dims<D>;
-  constexpr int DT = X::DT;
-  u32x2 vf[2][DT][2];
-  auto read_v = [&](auto ss) {
-    constexpr int S4 = decltype(ss)::value;
-    constexpr int OFF = (S4 >> 1) * 8192 + (S4 & 1) * 4096;
-    static_for<0, DT>([&](auto dd) {
-      constexpr int DTI = decltype(dd)::value;
-      vf[S4 & 1][DTI][0] = ds_read_tr_at<OFF>(tile_addr + (off ^ ((4 * DTI) << 4)));
-      vf[S4 & 1][DTI][1] = ds_read_tr_at<OFF + 2048>(tile_addr + (off ^ (((4 * DTI) ^ 2) << 4)));
-    });
-  };
-  read_v(std::integral_constant<int, 0>{});
-  make(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
-  static_for<0, 4>([&](auto ss) {
-    constexpr int S4 = decltype(ss)::value;
-    if constexpr (S4 + 1 < 4) read_v(std::integral_constant<int, S4 + 1>{});
-    lds_wait<(S4 + 1 < 4) ? 2 * DT : 0>();
-    const bf16x8 frag = __builtin_bit_cast(bf16x8, pw[S4]);
-    static_for<0, DT>([&](auto dd) {
-      constexpr int DTI = decltype(dd)::value;
-      tie(vf[S4 & 1][DTI][0]);
-      tie(vf[S4 & 1][DTI][1]);
-      const u32x4 a = {vf[S4 & 1][DTI][0][0], vf[S4 & 1][DTI][0][1], vf[S4 & 1][DTI][1][0], vf[S4 & 1][DTI][1][1]};
-      out[DTI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), frag, out[DTI], 0, 0, 0);
-      if constexpr (S4 + 1 < 4) {
-        make(std::integral_constant<int, S4 + 1>{}, std::integral_constant<int, (DTI * 4) / DT>{},
-             std::integral_constant<int, ((DTI + 1) * 4) / DT>{});
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    });
-  });
-}
-
 constexpr int RM_TILE = 16384;
 
 // ------------------------------------------------------------------------------------- dQ pass
 template <int D>
-DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
+DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int qb, int hh, int bi) {
   using X = Dims<D>;
   constexpr int STAGE = 2 * RM_TILE;                      // K tile, V tile (64 keys each)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  const int qb = nxb - 1 - xb;
-  const int hh = blockIdx.y, bi = blockIdx.z;
   const int s = p.seq;
   const int qw0 = qb * 128 + wave * 32, qpos = qw0 + fr;
   const long ld = p.ld;
@@ -528,37 +495,27 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
     const int kv0 = j * 64;
     if (kv0 > qw0 + 31) continue;
     const uint32_t st = smem_base + (j & 1) * STAGE;
-    // S^T = K Q^T; then dP^T = V dO^T with P^T = exp2(S^T sc - lse) formed between its MFMAs; then
-    // dQ^T += K^T dS^T fragment by fragment, dS^T = P^T (dP^T - D) of the next fragment between the MFMAs.
-    // The mask arithmetic runs only where the tile meets the diagonal.
-    auto tile = [&](auto masked) {
-      constexpr bool MASKED = decltype(masked)::value;
-      f32x16 sT[2], dpT[2];
+    f32x16 sT[2], dpT[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { sT[t][v] = 0.0f; dpT[t][v] = 0.0f; }
+    rm_mma_rows<D>(st, offP, qf, sT);                    // S^T  = K Q^T
+    rm_mma_rows<D>(st + RM_TILE, offP, dof, dpT);        // dP^T = V dO^T
+    auto probs = [&](auto masked) {                       // the mask arithmetic only where the tile meets the diagonal
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sT[t][v] = 0.0f; dpT[t][v] = 0.0f; }
-      rm_mma_rows<D>(st, offP, qf, sT, NoFill{});
-      rm_mma_rows<D>(st + RM_TILE, offP, dof, dpT, [&](auto ks) {
-        constexpr int CH = (32 + X::KSTEPS - 1) / X::KSTEPS, I0 = decltype(ks)::value * CH;
-#pragma unroll
-        for (int i = I0; i < I0 + CH && i < 32; ++i) {
-          const int t = i >> 4, v = i & 15;
+        for (int v = 0; v < 16; ++v) {
           float pr = exp2_raw(sT[t][v] * sc - lse2);
-          if (MASKED && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
-          sT[t][v] = pr;
+          if (decltype(masked)::value && kv0 + 32 * t + acc_row(v, fh) > qpos) pr = 0.0f;
+          sT[t][v] = pr * (dpT[t][v] - dq_dot);
         }
-      });
-      u32x4 dw[4];
-      rm_mma_cols_making<D>(st, offT, dw, dq, [&](auto ss, auto lo, auto hi) {
-        constexpr int S4 = decltype(ss)::value, t = S4 >> 1, b = 8 * (S4 & 1);
-#pragma unroll
-        for (int w = decltype(lo)::value; w < decltype(hi)::value; ++w)
-          dw[S4][w] = pack_bf16(sT[t][b + 2 * w] * (dpT[t][b + 2 * w] - dq_dot),
-                                sT[t][b + 2 * w + 1] * (dpT[t][b + 2 * w + 1] - dq_dot));
-      });
     };
-    if (kv0 + 63 > qw0) tile(std::true_type{}); else tile(std::false_type{});
+    if (kv0 + 63 > qw0) probs(std::true_type{}); else probs(std::false_type{});
+    bf16x8 dsf[4];
+    pack_acc_pair(sT, dsf);
+    rm_mma_cols<D>(st, offT, dsf, dq);                   // dQ^T += K^T dS^T
   }
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + qpos) * ld + hh * D;
@@ -568,15 +525,13 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int xb, int nxb) {
 
 // ------------------------------------------------------------------------------------- dK / dV pass
 template <int D>
-DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
+DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int kb, int hh, int bi) {
   using X = Dims<D>;
   constexpr int STAGE = 2 * RM_TILE + 512;                // Q tile, dO tile (64 queries), lse[64], dot[64]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  const int kb = xb;                              // 128 keys per workgroup
-  const int hh = blockIdx.y, bi = blockIdx.z;
-  const int s = p.seq;
+  const int s = p.seq;                            // 128 keys per workgroup
   const int kw0 = kb * 128 + wave * 32, kpos = kw0 + fr;
   const long ld = p.ld, ldc = p.ld_ctx;
   const bf16_t* tok0 = static_cast<const bf16_t*>(p.qkv) + (long)bi * s * ld;
@@ -630,8 +585,8 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) { sm[t][v] = 0.0f; dpm[t][v] = 0.0f; }
-    rm_mma_rows<D>(st, offP, kf, sm, NoFill{});           // S[q, kv]  = Q K^T
-    rm_mma_rows<D>(st + RM_TILE, offP, vf, dpm, NoFill{}); // dP[q, kv] = dO V^T
+    rm_mma_rows<D>(st, offP, kf, sm);                     // S[q, kv]  = Q K^T
+    rm_mma_rows<D>(st + RM_TILE, offP, vf, dpm);          // dP[q, kv] = dO V^T
     u32x4 pw[4], dw[4];                                   // P and dS rounded to bf16 as they are formed
     auto probs = [&](auto masked) {                       // the mask arithmetic only where the tile meets the diagonal
 #pragma unroll
@@ -680,17 +635,20 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int xb) {
 }
 
 
-// Both backward passes in one launch: workgroups [0, nxb) take the dK/dV pass of key block x (the longest
-// first), workgroups [nxb, 2 nxb) the dQ pass; the two are independent given D, so one launch puts twice
-// as many workgroups on the chip and the attention backward leaves its slice's critical path sooner.
+// Both backward passes in one launch (they are independent given D, so one launch puts twice as many
+// workgroups on the chip and the attention backward leaves its slice's critical path sooner).  Inside a
+// (batch, head) group the items alternate, longest first: dK/dV pass of key block 0, dQ pass of the last query
+// block, dK/dV pass of key block 1, ...
 template <int D>
 __global__ __launch_bounds__(256)
 void attn_bwd_kernel(const AttnArgs p) {
   extern __shared__ __align__(1024) uint8_t smem[];
-  const int nxb = gridDim.x >> 1;
-  const int xb = __builtin_amdgcn_readfirstlane(blockIdx.x);
-  if (xb < nxb) attn_bwd_dkv_body<D>(p, smem, xb);
-  else attn_bwd_dq_body<D>(p, smem, xb - nxb, nxb);
+  const int nxb = (p.seq + 127) / 128;
+  int pos, group;
+  if (!ranked_item(2 * nxb, p.heads * p.batch, pos, group)) return;
+  const int hh = group % p.heads, bi = group / p.heads;
+  if (pos & 1) attn_bwd_dq_body<D>(p, smem, nxb - 1 - (pos >> 1), hh, bi);
+  else attn_bwd_dkv_body<D>(p, smem, pos >> 1, hh, bi);
 }
 
 template <class K>
@@ -707,7 +665,7 @@ hipError_t fwd_launch(const AttnArgs& a, hipStream_t st) {
   static bool done = false;
   hipError_t e = set_lds(attn_fwd_kernel<D>, LDS, done);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_fwd_kernel<D>, dim3((a.seq + 127) / 128, a.heads, a.batch), dim3(256), LDS, st, a);
+  hipLaunchKernelGGL(attn_fwd_kernel<D>, dim3(ranked_grid((a.seq + 127) / 128, a.heads * a.batch)), dim3(256), LDS, st, a);
   return hipGetLastError();
 }
 
@@ -722,7 +680,7 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t st) {
   constexpr int LDS = 2 * (2 * RM_TILE + 512);             // the larger of the two passes' needs
   static bool done = false;
   if ((e = set_lds(attn_bwd_kernel<D>, LDS, done)) != hipSuccess) return e;
-  const dim3 grid(2 * ((a.seq + 127) / 128), a.heads, a.batch);
+  const dim3 grid(ranked_grid(2 * ((a.seq + 127) / 128), a.heads * a.batch));
   hipLaunchKernelGGL(attn_bwd_kernel<D>, grid, dim3(256), LDS, st, a);
   return hipGetLastError();
 }
