@@ -224,7 +224,7 @@ def _attn_inputs(rng, b, s, nh, d):
 
 
 @pytest.mark.parametrize("d", [64, 80, 128])
-@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3), (1, 64, 1), (1, 1, 1), (3, 9, 2)])   # s = 1: softmax over one key
+@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3), (1, 64, 1), (1, 1, 1), (3, 9, 2), (2, 640, 5)])   # s = 1: softmax over one key; the last: 50 / 100 work items dealt over 8 XCDs
 def test_attention_forward(dom, d, b, s, nh):
     rng = np.random.default_rng(d + s)
     hl = nh * d
@@ -243,7 +243,7 @@ def test_attention_forward(dom, d, b, s, nh):
 
 
 @pytest.mark.parametrize("d", [64, 80, 128])
-@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3), (1, 1, 1), (3, 9, 2)])
+@pytest.mark.parametrize("b,s,nh", [(2, 200, 2), (1, 384, 3), (1, 1, 1), (3, 9, 2), (2, 640, 5)])
 def test_attention_backward(dom, d, b, s, nh):
     rng = np.random.default_rng(d + s + 1)
     hl = nh * d
