@@ -267,6 +267,13 @@ int domino_profile_classes(void);
 const char* domino_profile_name(int cls);
 int domino_profile_read(int cls, double* total_ms, int* launches);
 int domino_profile_reset(void);
+/* The single launches behind those sums, in the order they were enqueued since the last reset:
+ * domino_profile_records() is their number; domino_profile_record() synchronises record `index`'s events and
+ * returns its step class, the stream it ran on (the handle the caller passed in) and its start and stop in
+ * milliseconds after the start of record 0 (negative if it began earlier on another stream).  Together they give
+ * the timeline of a step across the pool.  Errors: INVALID_ARG for an index out of range, NULL_POINTER, HIP. */
+int domino_profile_records(void);
+int domino_profile_record(int index, int* cls, void** stream, double* start_ms, double* stop_ms);
 
 const char* domino_last_error(void);   /* thread-local, static storage */
 const char* domino_version(void);

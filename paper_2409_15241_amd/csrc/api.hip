@@ -169,7 +169,7 @@ const char* const PROF_NAMES[PC_COUNT] = {
   "dgrad_down", "wgrad_down", "dgrad_up", "wgrad_up", "norm_bwd", "dgrad_out", "wgrad_out",
   "attn_bwd", "dgrad_qkv", "wgrad_qkv", "colsum"};
 
-struct ProfRec { int cls; hipEvent_t start, stop; };
+struct ProfRec { int cls; hipStream_t stream; hipEvent_t start, stop; };
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof_recs;
 std::vector<hipEvent_t> g_prof_free;
@@ -192,7 +192,7 @@ struct ProfScope {
   ~ProfScope() {
     if (!live) return;
     (void)hipEventRecord(stop, st);
-    g_prof_recs.push_back({cls, start, stop});
+    g_prof_recs.push_back({cls, st, start, stop});
   }
 };
 
@@ -936,6 +936,26 @@ int domino_profile_read(int cls, double* total_ms, int* launches) {
   }
   *total_ms = tot;
   *launches = n;
+  return DOMINO_OK;
+}
+
+int domino_profile_records(void) {
+  std::lock_guard<std::mutex> lock(g_mutex);
+  return (int)g_prof_recs.size();
+}
+
+int domino_profile_record(int index, int* cls, void** stream, double* start_ms, double* stop_ms) {
+  if (!cls || !stream || !start_ms || !stop_ms) return fail(DOMINO_ERR_NULL_POINTER, "an output pointer is NULL");
+  std::lock_guard<std::mutex> lock(g_mutex);
+  if (index < 0 || index >= (int)g_prof_recs.size()) return fail(DOMINO_ERR_INVALID_ARG, "record %d outside [0, %d)", index, (int)g_prof_recs.size());
+  const ProfRec& r = g_prof_recs[index];
+  const ProfRec& first = g_prof_recs[0];
+  HIP_TRY(hipEventSynchronize(first.start), "hipEventSynchronize");
+  HIP_TRY(hipEventSynchronize(r.stop), "hipEventSynchronize");
+  float a = 0.0f, b = 0.0f;
+  HIP_TRY(hipEventElapsedTime(&a, first.start, r.start), "hipEventElapsedTime");
+  HIP_TRY(hipEventElapsedTime(&b, first.start, r.stop), "hipEventElapsedTime");
+  *cls = r.cls; *stream = r.stream; *start_ms = a; *stop_ms = b;
   return DOMINO_OK;
 }
 

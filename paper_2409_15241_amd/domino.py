@@ -32,7 +32,8 @@ EXPORTS = (
     "domino_gemm", "domino_norm_fwd",
     "domino_norm_bwd_scratch_floats", "domino_norm_bwd", "domino_attention_fwd", "domino_attention_bwd",
     "domino_rope", "domino_colsum", "domino_profile_enable", "domino_profile_classes",
-    "domino_profile_name", "domino_profile_read", "domino_profile_reset", "domino_last_error",
+    "domino_profile_name", "domino_profile_read", "domino_profile_reset", "domino_profile_records",
+    "domino_profile_record", "domino_last_error",
     "domino_version", "domino_shutdown",
 )
 
@@ -116,6 +117,8 @@ def load() -> C.CDLL:
         "domino_profile_name": (C.c_char_p, [i32]),
         "domino_profile_read": (i32, [i32, C.POINTER(C.c_double), C.POINTER(i32)]),
         "domino_profile_reset": (i32, []),
+        "domino_profile_records": (i32, []),
+        "domino_profile_record": (i32, [i32, C.POINTER(i32), C.POINTER(C.c_void_p), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "domino_last_error": (C.c_char_p, []),
         "domino_version": (C.c_char_p, []),
         "domino_shutdown": (None, []),
@@ -340,3 +343,14 @@ def domino_profile_read(cls: int):
 
 def domino_profile_reset() -> None:
     _check(load().domino_profile_reset())
+
+
+def domino_profile_records() -> int:
+    return load().domino_profile_records()
+
+
+def domino_profile_record(index: int):
+    """(step class name, stream handle, start ms, stop ms) of profiled launch `index`, times after record 0's start."""
+    cls, st, a, b = C.c_int(), C.c_void_p(), C.c_double(), C.c_double()
+    _check(load().domino_profile_record(index, C.byref(cls), C.byref(st), C.byref(a), C.byref(b)))
+    return domino_profile_name(cls.value), st.value, a.value, b.value

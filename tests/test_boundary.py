@@ -132,6 +132,8 @@ def test_single_kernel_entry_points_validate():
     assert lib.domino_norm_bwd_scratch_floats(2048, 5120) == 2 * 128 * 5120
     assert lib.domino_profile_classes() >= 18 and lib.domino_profile_name(1) == b"gemm_qkv"
     assert lib.domino_profile_read(99, None, None) == domino.ERR_INVALID_ARG
+    assert lib.domino_profile_records() == 0
+    assert lib.domino_profile_record(0, None, None, None, None) == domino.ERR_NULL_POINTER
 
 
 def test_tuner_candidates_cut_exactly():

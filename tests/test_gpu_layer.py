@@ -214,3 +214,38 @@ def test_grid_search_returns_a_measured_setting(H):
     best, table = tune.tune(TINY, pairs=[(1, 1), (2, 2)], streams=(1, 2), steps=2, warmup=1)
     assert best in table and best[3] > 0.0
     assert {(p, q) for p, q, _, _ in table} == {(1, 1), (2, 2)}
+
+
+def test_profile_records_give_the_timeline_of_a_step(H):
+    """Every launch of a profiled step comes back with its step class, the pool stream it ran on and times that
+    are ordered on each stream; the per-class sums of domino_profile_read are the sums of these records."""
+    from paper_2409_15241_amd import domino as D
+    sc = TINY.replace(batch=4, p=4, q=2)
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    buf = H.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=4)
+    buf.forward(); buf.backward(); buf.sync()
+    D.domino_profile_reset()
+    D.domino_profile_enable(True)
+    try:
+        buf.forward(); buf.backward(); buf.sync()
+    finally:
+        D.domino_profile_enable(False)
+    n = D.domino_profile_records()
+    recs = [D.domino_profile_record(i) for i in range(n)]
+    assert n == sum(D.domino_profile_read(c)[1] for c in range(D.domino_profile_classes())) > 40
+    handles = {s.cuda_stream for s in buf.streams}
+    last = {}
+    for name, st, a, b in recs:
+        assert st in handles and b >= a
+        assert a >= last.get(st, -1e9)           # enqueue order is execution order on a stream
+        last[st] = b
+    for c in range(D.domino_profile_classes()):
+        tot, cnt = D.domino_profile_read(c)
+        mine = [b - a for name, _, a, b in recs if name == D.domino_profile_name(c)]
+        assert cnt == len(mine) and abs(tot - sum(mine)) <= 1e-3 * max(tot, 1e-3)
+    with pytest.raises(D.DominoError) as e:
+        D.domino_profile_record(n)
+    assert e.value.code == D.ERR_INVALID_ARG
+    D.domino_profile_reset()
+    assert D.domino_profile_records() == 0
