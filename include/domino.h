@@ -186,10 +186,9 @@ int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
 
 /* Backward of the stack for L = sum(y_last * dy): blocks nlayers-1 .. 0, dx of one being dy of the one below
  * (kept in the workspace).  grads[l] are block l's gradients (host array of nlayers structs); accumulate as
- * in domino_layer_bwd.  Within a block the weight gradients are still summed in slice order; between blocks a
- * slice goes on without waiting for the others, and each block's vector gradients are reduced on the last
- * slice's stream once all slices have left the block.  Results are bitwise those of nlayers calls of
- * domino_layer_bwd. */
+ * in domino_layer_bwd.  Within a block the weight and vector gradients are still summed in slice order (slice
+ * i's sum into a gradient waits for slice i-1's); between blocks a slice goes on without waiting for the
+ * others.  Results are bitwise those of nlayers calls of domino_layer_bwd. */
 int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* dy,
                      const domino_stack_bwd_io* io, void* dx, const domino_grads* grads, int accumulate,
                      void* workspace, size_t workspace_bytes, void* const* streams, int nstreams);

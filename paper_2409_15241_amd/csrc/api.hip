@@ -437,10 +437,10 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
 }
 
 // Weight gradients are summed over the row slices in slice order: slice i's product into a matrix waits for
-// slice i-1's product into the same matrix (one event per matrix).
+// slice i-1's product into the same matrix (one event per matrix; the fifth is for the vector gradients).
 struct WgChain {
   hipStream_t prev = nullptr;
-  hipEvent_t done[4] = {}, cur[4] = {};
+  hipEvent_t done[5] = {}, cur[5] = {};
 };
 
 // Backward of row slice i of one block; within the slice each input gradient is enqueued before the weight
@@ -554,31 +554,33 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   TRY(wgrad(3, PC_WGRAD_QKV, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
   if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, AREA_BQKV));
   }
-  if (parts & DOMINO_BWD_NORM1)
+  if (parts & DOMINO_BWD_NORM1) {
     TRY(norm_bwd(at(B.dln1_partial, rh), B.dln1_others ? at(B.dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
                  dx1, at(B.dx, rh), AREA_G1, AREA_B1));
+    // Vector gradients (norm gains and shifts, biases): the partial rows of all three parts of this slice lie in
+    // its block of the workspace now; one launch adds them to the gradients, after slice i-1's launch did
+    // (fixed order), so only the last slice's small sum is left at the end of the block.
+    if (chain) HIP_TRY(hipStreamWaitEvent(st, wg.done[4], 0), "hipStreamWaitEvent");
+    {
+      ProfScope ps(PC_COLSUM, st);
+      struct { int k; float* out; } vec[NAREAS] = {
+        {AREA_G1, G->norm1_g}, {AREA_B1, G->norm1_b}, {AREA_G2, G->norm2_g}, {AREA_B2, G->norm2_b},
+        {AREA_BQKV, G->b_qkv}, {AREA_BO, G->b_o}, {AREA_BUP, G->b_up}, {AREA_BDOWN, G->b_down}};
+      ColsumJobs jobs{};
+      int njobs = 0;
+      for (auto& v : vec) {
+        if (!v.out) continue;
+        if (L.llama && v.k != AREA_G1 && v.k != AREA_G2) continue;
+        jobs.job[njobs++] = {area(v.k), v.out, L.area_rows[v.k], L.area_n[v.k], (long)L.area_n[v.k], 1, 0L};
+      }
+      LAUNCH(colsum_finish_jobs_launch(jobs, njobs, beta, st), "vector gradient reduction");
+    }
+    TRY(next_sync_event(&wg.cur[4]));
+    HIP_TRY(hipEventRecord(wg.cur[4], st), "hipEventRecord");
+  }
 
   wg.prev = st;
-  for (int k = 0; k < 4; ++k) wg.done[k] = wg.cur[k];
-  return DOMINO_OK;
-}
-
-// vector gradients of one block: one launch sums, for every vector, the partial rows of all slices in slice order
-int enqueue_vector_grads(const Layout& L, const BwdLayer& B, hipStream_t st) {
-  ProfScope ps(PC_COLSUM, st);
-  const domino_grads* G = B.G;
-  struct { int k; float* out; } vec[NAREAS] = {
-    {AREA_G1, G->norm1_g}, {AREA_B1, G->norm1_b}, {AREA_G2, G->norm2_g}, {AREA_B2, G->norm2_b},
-    {AREA_BQKV, G->b_qkv}, {AREA_BO, G->b_o}, {AREA_BUP, G->b_up}, {AREA_BDOWN, G->b_down}};
-  ColsumJobs jobs{};
-  int njobs = 0;
-  for (auto& v : vec) {
-    if (!v.out) continue;
-    if (L.llama && v.k != AREA_G1 && v.k != AREA_G2) continue;
-    jobs.job[njobs++] = {B.red + L.area_off[v.k], v.out, L.area_rows[v.k], L.area_n[v.k], (long)L.area_n[v.k],
-                         L.p, (long)L.red_floats};
-  }
-  LAUNCH(colsum_finish_jobs_launch(jobs, njobs, B.accumulate, st), "vector gradient reduction");
+  for (int k = 0; k < 5; ++k) wg.done[k] = wg.cur[k];
   return DOMINO_OK;
 }
 
@@ -701,8 +703,6 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   WgChain wg;
   for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), B, i, wg, parts));
   TRY(join_streams(S, used));
-  // the partial sums of all three parts lie in the workspace by the time the last part has run
-  if (parts & DOMINO_BWD_NORM1) TRY(enqueue_vector_grads(L, B, as_stream(streams[0])));
   return DOMINO_OK;
 }
 
@@ -777,14 +777,9 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   const StreamPlan S(streams, nstreams, L.p, 1);
   const std::vector<char> used = S.used_fwd();
   TRY(fork_streams(S, used));
-  hipStream_t last = S.slice(L.p - 1);
   for (int l = nlayers - 1; l >= 0; --l) {
     WgChain wg;
     for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), layers[l], i, wg));
-    // the block's vector gradients need every slice: they go on the last slice's stream, which the chain of
-    // weight gradients already makes the last to finish the block
-    for (int k = 0; k < S.nslice; ++k) TRY(edge(as_stream(streams[k]), last));
-    TRY(enqueue_vector_grads(L, layers[l], last));
   }
   TRY(join_streams(S, used));
   return DOMINO_OK;
