@@ -96,9 +96,9 @@ int domino_saved_slot(const domino_cfg* cfg, const char* name, size_t* offset, s
  *   attn_others, mlp_others: [b,s,h] or NULL (= zeros): sum of the other ranks' partials.
  *   attn_partial, mlp_partial: out [b,s,h]: what the two forward all-reduces would consume.
  *   y: out [b,s,h] or NULL.   saved: out, domino_saved_bytes().   workspace: scratch.
- *   streams[0..nstreams-1]: row slice i runs on streams[i % min(nstreams, p)]; with nstreams >= p*q the
- *   column piece (i, j > 0) runs on streams[i + j*p] (forked from and joined to its slice's stream),
- *   otherwise on its slice's stream.  Slices overlap only if their streams sit on distinct hardware queues: create
+ *   streams[0..nstreams-1]: row slice i, with its q column pieces in index order, runs on
+ *   streams[i % min(nstreams, p)]; streams beyond the first min(nstreams, p) are not used.
+ *   Slices overlap only if their streams sit on distinct hardware queues: create
  *   the pool once, and let the process have more hardware queues than the pool has streams (HIP's
  *   GPU_MAX_HW_QUEUES, read when the runtime starts). */
 int domino_layer_fwd(const domino_cfg* cfg, const domino_params* params,

@@ -270,20 +270,17 @@ struct BwdLayer {
 };
 
 // which stream of the pool carries which piece (Sec. 4.3.1: a fixed pool, picked by index)
+// Row slice i runs on streams[i % nslice] with all its column pieces: on one GPU there is no all-reduce for a
+// piece to overlap, and pieces on streams of their own were measured slower (the slices already fill the chip).
 struct StreamPlan {
   void* const* streams;
-  int ns, p, q, nslice;
-  bool wide;                                                // enough streams for every column piece
-  StreamPlan(void* const* s, int n, int p_, int q_)
-      : streams(s), ns(n), p(p_), q(q_), nslice(p_ < n ? p_ : n), wide(n >= p_ * q_) {}
-  int piece_index(int i, int j) const { return (wide && j > 0) ? i + j * p : i % nslice; }
+  int ns, p, nslice;
+  StreamPlan(void* const* s, int n, int p_) : streams(s), ns(n), p(p_), nslice(p_ < n ? p_ : n) {}
   hipStream_t slice(int i) const { return as_stream(streams[i % nslice]); }
-  hipStream_t piece(int i, int j) const { return as_stream(streams[piece_index(i, j)]); }
-  // streams that a forward call touches; the backward touches the first nslice only
-  std::vector<char> used_fwd() const {
+  // streams that a call touches: the first nslice
+  std::vector<char> used() const {
     std::vector<char> u(ns, 0);
-    for (int i = 0; i < p; ++i)
-      for (int j = 0; j < q; ++j) u[piece_index(i, j)] = 1;
+    for (int k = 0; k < nslice; ++k) u[k] = 1;
     return u;
   }
 };
@@ -381,16 +378,13 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
   }
   // F4: (XA) * B_j, one piece per column slice, written in place into the full-width buffer
   for (int j = 0; j < L.q; ++j) {
-    hipStream_t sj = S.piece(i, j);
-    TRY(edge(st, sj));
     {
-      ProfScope ps(PC_GEMM_OUT, sj);
+      ProfScope ps(PC_GEMM_OUT, st);
       const size_t cj = (size_t)j * L.hq * 2;
       GemmArgs a = gemm_args(ctx, L.hl, at(P->w_o, cj), L.h, at(B.attn_partial, rh + cj), L.h, Ms, L.hq, L.hl);
-      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "out-projection piece");
+      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "out-projection piece");
     }
-    TRY(edge(sj, st));                                    // column synchronisation before Norm2
-  }
+  }                                                       // column synchronisation before Norm2: stream order
   }
   if (!(parts & DOMINO_FWD_MLP)) return DOMINO_OK;
   {  // F5: residual + reduced attention output + Norm2
@@ -409,15 +403,10 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
     else { a.bias = P->b_up; LAUNCH(gemm_launch(GEMM_NN, EPI_BIAS_GELU, a, -1, st), "mlp-up product"); }
   }
   for (int j = 0; j < L.q; ++j) {  // F7
-    hipStream_t sj = S.piece(i, j);
-    TRY(edge(st, sj));
-    {
-      ProfScope ps(PC_GEMM_DOWN, sj);
-      const size_t cj = (size_t)j * L.hq * 2;
-      GemmArgs a = gemm_args(act, L.fl, at(P->w_down, cj), L.h, at(B.mlp_partial, rh + cj), L.h, Ms, L.hq, L.fl);
-      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, sj), "mlp-down piece");
-    }
-    TRY(edge(sj, st));
+    ProfScope ps(PC_GEMM_DOWN, st);
+    const size_t cj = (size_t)j * L.hq * 2;
+    GemmArgs a = gemm_args(act, L.fl, at(P->w_down, cj), L.h, at(B.mlp_partial, rh + cj), L.h, Ms, L.hq, L.fl);
+    LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "mlp-down piece");
   }
   if (next) {  // F8 of this block and F1 of the next in one pass over the rows: y is written and normalised at once
     ProfScope ps(PC_NORM_FWD, st);
@@ -658,8 +647,8 @@ int domino_layer_fwd_parts(const domino_cfg* cfg, const domino_params* P,
   TRY(begin_call());
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
-  const StreamPlan S(streams, nstreams, L.p, L.q);
-  const std::vector<char> used = S.used_fwd();
+  const StreamPlan S(streams, nstreams, L.p);
+  const std::vector<char> used = S.used();
   TRY(fork_streams(S, used));
   for (int i = 0; i < L.p; ++i) TRY(enqueue_fwd_slice(L, cfg, S, B, i, parts));
   TRY(join_streams(S, used));
@@ -697,8 +686,8 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   B.red = reinterpret_cast<float*>(at(workspace, L.red));
-  const StreamPlan S(streams, nstreams, L.p, 1);            // the backward uses the slice streams only
-  const std::vector<char> used = S.used_fwd();
+  const StreamPlan S(streams, nstreams, L.p);
+  const std::vector<char> used = S.used();
   TRY(fork_streams(S, used));
   WgChain wg;
   for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), B, i, wg, parts));
@@ -738,8 +727,8 @@ int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
 
   // a row slice of block l+1 needs only the same row slice of block l (Sec. 3.2): the slices run through the
   // whole stack on their own streams and meet only at the end
-  const StreamPlan S(streams, nstreams, L.p, L.q);
-  const std::vector<char> used = S.used_fwd();
+  const StreamPlan S(streams, nstreams, L.p);
+  const std::vector<char> used = S.used();
   TRY(fork_streams(S, used));
   for (int l = 0; l < nlayers; ++l)
     for (int i = 0; i < L.p; ++i)
@@ -774,8 +763,8 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   TRY(begin_call());
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
-  const StreamPlan S(streams, nstreams, L.p, 1);
-  const std::vector<char> used = S.used_fwd();
+  const StreamPlan S(streams, nstreams, L.p);
+  const std::vector<char> used = S.used();
   TRY(fork_streams(S, used));
   for (int l = nlayers - 1; l >= 0; --l) {
     WgChain wg;
