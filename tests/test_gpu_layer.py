@@ -249,3 +249,39 @@ def test_profile_records_give_the_timeline_of_a_step(H):
     assert e.value.code == D.ERR_INVALID_ARG
     D.domino_profile_reset()
     assert D.domino_profile_records() == 0
+
+
+def test_two_host_threads_with_their_own_pools(H):
+    """Two host threads enqueue steps at the same time, each on its own buffers and stream pool: the library
+    serialises the enqueueing (one mutex, one event pool per device) and every result has the bits of a
+    single-threaded run."""
+    import threading
+    sc = TINY.replace(batch=4, p=2, q=2)
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    others = synth.make_others(sc)
+    ref = run_gpu(H, sc, params, x, dy, others, nstreams=2)
+    bufs = [H.LayerBuffers(sc, params, x, dy, others, nstreams=2) for _ in range(2)]
+    errors = []
+
+    def work(buf):
+        try:
+            for _ in range(25):
+                buf.forward()
+                buf.backward(accumulate=False)
+            buf.sync()
+        except Exception as e:          # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(b,)) for b in bufs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not errors and not any(t.is_alive() for t in threads)
+    for b in bufs:
+        np.testing.assert_array_equal(H.to_host_f64(b.y), ref["y"])
+        np.testing.assert_array_equal(H.to_host_f64(b.dx), ref["dx"])
+        for k, g in b.grads.items():
+            if g is not None:
+                np.testing.assert_array_equal(g.cpu().numpy(), ref["grads"][k], err_msg=k)
