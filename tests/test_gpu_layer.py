@@ -285,3 +285,45 @@ def test_two_host_threads_with_their_own_pools(H):
         for k, g in b.grads.items():
             if g is not None:
                 np.testing.assert_array_equal(g.cpu().numpy(), ref["grads"][k], err_msg=k)
+
+
+def test_graph_replay_is_bitwise_the_eager_step(H):
+    """The step captured once in a HIP graph on streams[0] (the library forks and joins the pool inside the capture,
+    allocates nothing and records no memset) and replayed several times, with eager steps and synchronisations in
+    between: every replay leaves the bits of the eager step."""
+    sc = TINY.replace(batch=4, p=4, q=2)
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    others = synth.make_others(sc)
+    ref = run_gpu(H, sc, params, x, dy, others, nstreams=4)
+    buf = H.LayerBuffers(sc, params, x, dy, others, nstreams=4)
+    other = H.LayerBuffers(sc, params, x, dy, others, nstreams=4)       # eager work between the replays
+
+    def step():
+        buf.forward()
+        buf.backward(accumulate=False)
+
+    step()
+    buf.sync()
+    s0 = buf.streams[0]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s0):
+        step()
+    for rep in range(4):
+        for t in (buf.y, buf.dx, buf.attn_partial, buf.mlp_partial, buf.dln1_partial, buf.dln2_partial):
+            t.zero_()
+        for g in buf.grads.values():
+            if g is not None:
+                g.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s0):
+            graph.replay()
+        torch.cuda.synchronize()
+        for k in ("attn_partial", "mlp_partial", "y", "dln2_partial", "dln1_partial", "dx"):
+            np.testing.assert_array_equal(H.to_host_f64(getattr(buf, k)), ref[k], err_msg=f"replay {rep}: {k}")
+        for k, g in buf.grads.items():
+            if g is not None:
+                np.testing.assert_array_equal(g.cpu().numpy(), ref["grads"][k], err_msg=f"replay {rep}: {k}")
+        other.forward()
+        other.backward(accumulate=False)
+        other.sync()
