@@ -65,6 +65,83 @@ def measured_traffic(workload, kernel):
     return None
 
 
+def draw_inputs(sc):
+    """The seeded inputs of a workload; the three groups of tensors are drawn side by side (NumPy's generators
+    release the interpreter lock), which changes no value: every tensor has a random stream of its own."""
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2409_15241_amd import synth
+    with ThreadPoolExecutor(max_workers=3) as ex:
+        fp = ex.submit(synth.make_rank_params, sc)
+        fa = ex.submit(synth.make_activations, sc)
+        fo = ex.submit(synth.make_others, sc)
+        x, dy = fa.result()
+        return fp.result(), x, dy, fo.result()
+
+
+def time_other_workloads(names, nstreams, pool, steps=10, warmup=3):
+    """Forward + backward of the other configured shards as configured (their p and q), event-timed on the pool's
+    first stream over `steps` steps in a row after `warmup` steps: ms per step, TFLOP/s, % of the nominal peak."""
+    import torch
+    from paper_2409_15241_amd import harness, synth
+    out = {}
+    for name in names:
+        sc = synth.WORKLOADS[name]
+        params, x, dy, others = draw_inputs(sc)
+        buf = harness.LayerBuffers(sc, params, x, dy, others, streams=pool[:nstreams])
+        del params, x, dy, others
+        for _ in range(warmup):
+            buf.forward()
+            buf.backward(False)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(buf.streams[0])
+        for _ in range(steps):
+            buf.forward()
+            buf.backward(False)
+        e1.record(buf.streams[0])
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        tf = algorithmic_flops(sc) / (ms * 1e-3) / 1e12
+        out[name] = {"ms_per_step": ms, "value": tf, "unit": "TFLOP/s", "pct_of_bf16_mfma_peak": 100.0 * tf / BF16_MFMA_PEAK_TFLOPS,
+                     "p": sc.p, "q": sc.q, "tokens": sc.tokens, "steps": steps}
+        del buf
+        torch.cuda.empty_cache()
+    return out
+
+
+def measured_mfma_ceiling(stream, seconds=0.06):
+    """TFLOP/s of back-to-back bf16 MFMAs (the library's MFMA-only probe) on operands drawn like the layer's
+    (activations ~ N(0,1) against weights ~ N(0, 0.02^2)), sustained for about `seconds` so that the clock has
+    settled where the power limit puts it."""
+    import torch
+    from paper_2409_15241_amd import domino
+    g = torch.Generator(device="cuda").manual_seed(20240915)
+    a = torch.randn(2048, device="cuda", generator=g).to(torch.bfloat16)
+    b = (0.02 * torch.randn(2048, device="cuda", generator=g)).to(torch.bfloat16)
+    blocks = 512                       # two workgroups of four waves per compute unit
+    out = torch.empty(blocks * 256, device="cuda", dtype=torch.float32)
+    torch.cuda.synchronize()
+    iters = 2000
+    domino.domino_mfma_probe(a, b, out, blocks, iters, stream)          # warm-up and a first rate
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    fl = domino.domino_mfma_probe(a, b, out, blocks, iters, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    per_iter_ms = e0.elapsed_time(e1) / iters
+    n = max(1, int(seconds * 1e3 / 6 / per_iter_ms))                    # six launches fill the span
+    tot_fl = 0.0
+    e0.record(stream)
+    for k in range(6):
+        if k == 2:
+            e0.record(stream)                                           # the first two launches let the clock settle
+            tot_fl = 0.0
+        tot_fl += domino.domino_mfma_probe(a, b, out, blocks, n, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return tot_fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def cpu_baseline(sc, budget_s=30.0):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
     import numpy as np
@@ -114,6 +191,9 @@ def main():
     ap.add_argument("--stack-layers", type=int, default=4,
                     help="with --layers 1: also time a stack of this many blocks (0 = skip) and report it under 'stack'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the 10 timed steps of each of the other configured shards (key 'other_workloads')")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the MFMA-only probe (key 'measured_mfma_ceiling')")
     ap.add_argument("--no-roofline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-step-class timing table to stderr")
     ap.add_argument("--copy-check", type=int, default=0, metavar="MIB",
@@ -128,15 +208,17 @@ def main():
     import torch
     from paper_2409_15241_amd import domino, harness, synth
     domino.load()
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(3)
     sc = synth.WORKLOADS[args.workload]
     if args.p or args.q:
         sc = sc.replace(p=args.p or sc.p, q=args.q or sc.q)
-    params = synth.make_rank_params(sc)
-    x, dy = synth.make_activations(sc)
-    others = synth.make_others(sc)
+    if args.graph and not domino.domino_capture_supported(args.streams, sc.p):
+        print("bench.py: --graph is limited to pools of 1, 2 or 4 streams (graph instantiation of the other pool "
+              "sizes aborted inside the runtime on this ROCm; the library refuses to be captured with them)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    params, x, dy, others = draw_inputs(sc)
     if args.layers > 1:
         params_l, others_l = synth.make_stack(sc, args.layers)
         buf = harness.StackBuffers(sc, params_l, x, dy, others_l, nstreams=args.streams)
@@ -149,10 +231,6 @@ def main():
         buf.backward(accumulate=False)
 
     step = eager_step
-    if args.graph and args.streams not in (2, 4):
-        print("bench.py: --graph is limited to pools of 2 or 4 streams (graph instantiation of the other pool "
-              "sizes crashed inside the runtime on this ROCm)", file=sys.stderr)
-        sys.exit(2)
     if args.graph:
         # one pass of the path captured once on streams[0] (the library forks the other streams from it
         # and joins them back) and replayed: same kernels, launch order fixed by the graph's edges
@@ -201,13 +279,14 @@ def main():
 
     roofline = None
     if not args.no_roofline:
-        # the same K steps again with every launch bracketed by timing events on its own stream
+        # the same K steps again with every launch bracketed by timing events on its own stream (eagerly also
+        # when the timed steps were graph replays: a replay makes no library call that could be bracketed)
         domino.domino_profile_reset()
         domino.domino_profile_enable(True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            step()
+            eager_step()
         torch.cuda.synchronize()
         inst_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         domino.domino_profile_enable(False)
@@ -241,6 +320,9 @@ def main():
         roofline = {"bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                     "traffic": measured_traffic(sc.name, dom_name),
+                    "traffic_source": "profiles/hbm_traffic_per_launch.md: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of "
+                                      "this kernel at this workload's shapes, scaled by a plain copy of known size; not "
+                                      "re-measured by this run (null: no such run for this workload)",
                     "avg_launch_us": avg_ms * 1e3, "launches_per_step": n // args.steps,
                     "flops_per_launch": f / n, "ms_per_step_instrumented": inst_ms}
         if args.breakdown:
@@ -296,6 +378,15 @@ def main():
         stack = {"layers": nl, "ms_per_step": sms, "ms_per_layer": sms / nl,
                  "value": algorithmic_flops(sc) * nl / (sms * 1e-3) / 1e12, "unit": "TFLOP/s"}
 
+    ceiling = None if args.no_ceiling else measured_mfma_ceiling(s0)
+    pool = buf.streams
+    others_wl = None
+    if not args.no_other_workloads and args.layers == 1:
+        del buf
+        torch.cuda.empty_cache()
+        names = [n for n in ("tiny", "gpt3-2.7b", "gpt3-13b", "llama2-7b", "llama2-13b") if n != sc.name]
+        others_wl = time_other_workloads(names, args.streams, pool)
+
     cpu = None if args.no_cpu_baseline else cpu_baseline(sc)
 
     line = {
@@ -309,6 +400,11 @@ def main():
         "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "algorithmic_gflop_per_step": flops / 1e9, "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
         "ms_per_step_max": ms_max, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,
+        "measured_mfma_ceiling": None if ceiling is None else {
+            "value": ceiling, "unit": "TFLOP/s",
+            "what": "back-to-back 32x32x16 bf16 MFMAs on N(0,1) x N(0,0.02) fragments, nothing else running (domino_mfma_probe)"},
+        "pct_of_measured_mfma_ceiling": None if ceiling is None else 100.0 * value / ceiling,
+        "other_workloads": others_wl,
         "stack": stack, "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

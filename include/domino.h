@@ -73,11 +73,14 @@ typedef struct domino_grads {
         *norm2_g, *norm2_b, *w_up, *b_up, *w_down, *b_down;
 } domino_grads;
 
-/* Host-only checks of a configuration (no GPU call).  Returns DOMINO_OK or the error. */
+/* Host-only checks of a configuration (no GPU call): the cuts of Sec. 4.1.1 (batch into p1 parts) and Sec. 4.2
+ * (hidden into p2 parts) and the tensor-parallel split of Sec. 3.1 must be exact.  Returns DOMINO_OK or the error. */
 int domino_validate_cfg(const domino_cfg* cfg);
 
 /* Bytes of the activation block carried from forward to backward, and of the scratch workspace
- * either call needs (0 on an invalid cfg).  Both are caller-allocated, 256-byte aligned. */
+ * either call needs (0 on an invalid cfg).  Both are caller-allocated, 256-byte aligned: like the
+ * pre-allocated full-width output buffer of Sec. 4.2 into which the column pieces are written, every
+ * buffer of the path exists before the call and the library allocates none. */
 size_t domino_saved_bytes(const domino_cfg* cfg);
 size_t domino_workspace_bytes(const domino_cfg* cfg);
 
@@ -100,7 +103,9 @@ int domino_saved_slot(const domino_cfg* cfg, const char* name, size_t* offset, s
  *   streams[i % min(nstreams, p)]; streams beyond the first min(nstreams, p) are not used.
  *   Slices overlap only if their streams sit on distinct hardware queues: create
  *   the pool once, and let the process have more hardware queues than the pool has streams (HIP's
- *   GPU_MAX_HW_QUEUES, read when the runtime starts). */
+ *   GPU_MAX_HW_QUEUES, read when the runtime starts; domino_last_warning() tells when it looks too small).
+ *   streams[0] may be under HIP graph capture (the other streams join the capture through the call's own
+ *   fork and leave it at its join) for the pools domino_capture_supported() accepts. */
 int domino_layer_fwd(const domino_cfg* cfg, const domino_params* params,
                      const void* x, const void* attn_others, const void* mlp_others,
                      void* attn_partial, void* mlp_partial, void* y,
@@ -254,6 +259,13 @@ int domino_rope(void* m, int64_t ld, int rows, int seq, int col0, int nblocks, i
 int domino_colsum(const void* g, int64_t ld, int rows, int n, float* out, int accumulate,
                   float* scratch, void* stream);
 
+/* MFMA-only probe for the "share of the measured matrix ceiling" figure that goes beside the share of the nominal
+ * peak (the paper's metric is throughput, Sec. 5.2; a roofline needs the ceiling the chip really sustains): `blocks`
+ * workgroups of 4 waves, every wave issuing iters x 8 independent 32x32x16 bf16 MFMAs back to back on one A and
+ * one B fragment per lane taken from a and b (bf16 [2048] each, caller-filled with the data distribution to
+ * probe).  out: fp32 [blocks * 256], receives accumulator sums.  *flops (may be NULL) = flops of the launch. */
+int domino_mfma_probe(const void* a, const void* b, float* out, int blocks, int iters, double* flops, void* stream);
+
 /* ---- instrumentation -------------------------------------------------------------------------- */
 
 /* While enabled, every kernel launched by domino_layer_fwd/bwd is bracketed by a pair of timing
@@ -275,6 +287,20 @@ int domino_profile_records(void);
 int domino_profile_record(int index, int* cls, void** stream, double* start_ms, double* stop_ms);
 
 const char* domino_last_error(void);   /* thread-local, static storage */
+
+/* A note about a condition that costs time without changing results, or "" if there is none (process-wide,
+ * static storage, written at most once per condition).  Today: a layer or stack call that puts 4 or more row
+ * slices on streams of their own while GPU_MAX_HW_QUEUES, as found in the environment, is unset or below the
+ * number of those streams + 1 (Sec. 4.3.1 keeps a fixed pool of streams; on this runtime two streams that share a
+ * hardware queue run their slices one after the other: 3.7-4.0 ms instead of 2.6 ms per step on the 13B shard).
+ * The runtime reads the variable when it starts, so the library can only report it. */
+const char* domino_last_warning(void);
+
+/* Whether layer and stack calls may be recorded into a HIP graph (Sec. 4.3.2) with a pool of nstreams streams
+ * and p row slices: 1 or 0, host-only.  Replays are bitwise the eager step for pools of 1, 2 or 4 streams of
+ * which 1, 2 or 4 carry slices.  A call whose streams[0] is being captured with any other pool returns
+ * DOMINO_ERR_UNSUPPORTED before it enqueues anything (instantiating such a graph has aborted inside the runtime). */
+int domino_capture_supported(int nstreams, int p);
 const char* domino_version(void);
 void domino_shutdown(void);            /* destroys cached events; the library stays usable */
 

@@ -10,6 +10,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -19,6 +20,7 @@
 #include "eltwise.h"
 #include "gemm.h"
 #include "norm.h"
+#include "probe.h"
 
 namespace {
 
@@ -39,6 +41,29 @@ int fail_hip(hipError_t e, const char* what) {
     hipError_t e_ = (expr);                                  \
     if (e_ != hipSuccess) return fail_hip(e_, what);         \
   } while (0)
+
+// One-time notes about conditions that do not change results but cost time (process-wide, see domino_last_warning).
+std::mutex g_warn_mutex;
+char g_warn[512] = "";
+bool g_warned_queues = false;
+
+// The pool's streams overlap only if each sits on a hardware queue of its own.  The HIP runtime reads
+// GPU_MAX_HW_QUEUES once, when it starts (default 4, one of which serves the null stream), so all the library can do
+// is look at the environment the process was started with and say what it sees.
+void note_hw_queues(int nslice) {
+  if (nslice < 4) return;
+  std::lock_guard<std::mutex> lock(g_warn_mutex);
+  if (g_warned_queues) return;
+  const char* env = getenv("GPU_MAX_HW_QUEUES");
+  const int have = env ? atoi(env) : 0;
+  if (have >= nslice + 1) return;
+  g_warned_queues = true;
+  snprintf(g_warn, sizeof(g_warn),
+           "%d row slices run on %d streams but GPU_MAX_HW_QUEUES is %s%s: with fewer hardware queues than streams + 1 "
+           "two pool streams share a queue and their slices run one after the other (measured 3.7-4.0 ms instead of "
+           "2.6 ms per step on the 13B shard); set GPU_MAX_HW_QUEUES >= %d before the HIP runtime starts",
+           nslice, nslice, env ? "" : "unset (runtime default 4)", env ? env : "", nslice + 1);
+}
 
 constexpr size_t ALIGN = 256;
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
@@ -141,11 +166,31 @@ struct EventPool { std::vector<hipEvent_t> events; size_t used = 0; };
 std::map<int, EventPool> g_pools;
 EventPool* g_pool = nullptr;               // the current device's pool, set by begin_call()
 
-int begin_call() {
+// Pools under which a layer or stack call has been replayed from a HIP graph bit for bit: 1, 2 or 4 streams, with
+// 1, 2 or 4 of them carrying slices.  Instantiating a graph captured with a pool of 3 or 8 streams has aborted
+// inside the runtime; until the reason is known such captures are refused before anything is enqueued.
+bool capture_pool_ok(int nstreams, int p) {
+  const int nslice = p < nstreams ? p : nstreams;
+  auto ok = [](int v) { return v == 1 || v == 2 || v == 4; };
+  return ok(nstreams) && ok(nslice);
+}
+
+int begin_call(void* const* streams, int nstreams, int p) {
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
   g_pool = &g_pools[dev];
-  g_pool->used = 0;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  HIP_TRY(hipStreamIsCapturing(static_cast<hipStream_t>(streams[0]), &cs), "hipStreamIsCapturing");
+  if (cs != hipStreamCaptureStatusNone) {
+    if (!capture_pool_ok(nstreams, p))
+      return fail(DOMINO_ERR_UNSUPPORTED, "streams[0] is being captured into a HIP graph with a pool of %d streams for %d row "
+                  "slices: capture is supported for pools of 1, 2 or 4 streams only (see domino_capture_supported)", nstreams, p);
+    // every edge of one capture keeps an event of its own: the calls recorded into a capture (a forward and a
+    // backward, say) never re-record an event that an earlier call of the same capture recorded
+  } else {
+    g_pool->used = 0;
+  }
+  note_hw_queues(p < nstreams ? p : nstreams);
   return DOMINO_OK;
 }
 
@@ -593,6 +638,13 @@ constexpr int MAX_STACK_LAYERS = 1024;
 extern "C" {
 
 const char* domino_last_error(void) { return g_err; }
+const char* domino_last_warning(void) {
+  std::lock_guard<std::mutex> lock(g_warn_mutex);
+  return g_warn;
+}
+int domino_capture_supported(int nstreams, int p) {
+  return (nstreams >= 1 && p >= 1 && capture_pool_ok(nstreams, p)) ? 1 : 0;
+}
 const char* domino_version(void) { return "domino-mi355x 0.1 (gfx950)"; }
 
 int domino_validate_cfg(const domino_cfg* cfg) { return validate(cfg, nullptr); }
@@ -644,7 +696,7 @@ int domino_layer_fwd_parts(const domino_cfg* cfg, const domino_params* P,
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
-  TRY(begin_call());
+  TRY(begin_call(streams, nstreams, L.p));
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   const StreamPlan S(streams, nstreams, L.p);
@@ -682,7 +734,7 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
-  TRY(begin_call());
+  TRY(begin_call(streams, nstreams, L.p));
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   B.red = reinterpret_cast<float*>(at(workspace, L.red));
@@ -722,7 +774,7 @@ int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < need) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, need);
   std::lock_guard<std::mutex> lock(g_mutex);
-  TRY(begin_call());
+  TRY(begin_call(streams, nstreams, L.p));
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   // a row slice of block l+1 needs only the same row slice of block l (Sec. 3.2): the slices run through the
@@ -760,7 +812,7 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   }
   TRY(check_streams(streams, nstreams));
   std::lock_guard<std::mutex> lock(g_mutex);
-  TRY(begin_call());
+  TRY(begin_call(streams, nstreams, L.p));
   ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
 
   const StreamPlan S(streams, nstreams, L.p);
@@ -892,6 +944,15 @@ int domino_colsum(const void* g, int64_t ld, int rows, int n, float* out, int ac
   hipStream_t st = as_stream(stream);
   HIP_TRY(colsum_partial_launch(g, ld, rows, n, scratch, st), "colsum launch");
   HIP_TRY(colsum_finish_launch(scratch, COLSUM_PARTS, n, out, accumulate, st), "colsum launch");
+  return DOMINO_OK;
+}
+
+int domino_mfma_probe(const void* a, const void* b, float* out, int blocks, int iters, double* flops, void* stream) {
+  if (!a || !b || !out) return fail(DOMINO_ERR_NULL_POINTER, "a, b or out is NULL");
+  if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24))
+    return fail(DOMINO_ERR_INVALID_ARG, "blocks must lie in [1, 65536] and iters in [1, 2^24]");
+  if (flops) *flops = (double)blocks * 4.0 * iters * MFMA_PROBE_FLOPS_PER_WAVE_ITER;
+  HIP_TRY(mfma_probe_launch(a, b, out, blocks, iters, as_stream(stream)), "mfma probe launch");
   return DOMINO_OK;
 }
 

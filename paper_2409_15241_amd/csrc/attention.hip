@@ -18,6 +18,7 @@
 //     dS = P (dP - D), dK^T += Q^T dS.
 // D[q] = sum_d dO[q,d] O[q,d] comes from a small pre-pass.
 #include "attention.h"
+#include "host_once.h"
 #include "lds_dma.h"
 #include <type_traits>
 
@@ -651,19 +652,12 @@ void attn_bwd_kernel(const AttnArgs p) {
   else attn_bwd_dkv_body<D>(p, smem, pos >> 1, hh, bi);
 }
 
-template <class K>
-hipError_t set_lds(K kern, int bytes, bool& done) {
-  if (done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-  if (e == hipSuccess) done = true;
-  return e;
-}
 
 template <int D>
 hipError_t fwd_launch(const AttnArgs& a, hipStream_t st) {
   constexpr int LDS = 2 * (((D + 31) / 32) * 4096 + 2 * 8192);
-  static bool done = false;
-  hipError_t e = set_lds(attn_fwd_kernel<D>, LDS, done);
+  static LdsLimitOnce lds_limit;
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void*>(attn_fwd_kernel<D>), LDS);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_fwd_kernel<D>, dim3(ranked_grid((a.seq + 127) / 128, a.heads * a.batch)), dim3(256), LDS, st, a);
   return hipGetLastError();
@@ -678,8 +672,8 @@ hipError_t bwd_launch(const AttnArgs& a, hipStream_t st) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   constexpr int LDS = 2 * (2 * RM_TILE + 512);             // the larger of the two passes' needs
-  static bool done = false;
-  if ((e = set_lds(attn_bwd_kernel<D>, LDS, done)) != hipSuccess) return e;
+  static LdsLimitOnce lds_limit;
+  if ((e = lds_limit.ensure(reinterpret_cast<const void*>(attn_bwd_kernel<D>), LDS)) != hipSuccess) return e;
   const dim3 grid(ranked_grid(2 * ((a.seq + 127) / 128), a.heads * a.batch));
   hipLaunchKernelGGL(attn_bwd_kernel<D>, grid, dim3(256), LDS, st, a);
   return hipGetLastError();

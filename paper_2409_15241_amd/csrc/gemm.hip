@@ -18,6 +18,7 @@
 // with 4 consecutive n for one m: 8-byte bf16 / 16-byte fp32 stores.
 #include "gemm.h"
 #include <cmath>
+#include "host_once.h"
 #include "lds_dma.h"
 #include <type_traits>
 
@@ -322,13 +323,8 @@ hipError_t launch_cfg(const GemmArgs& a0, hipStream_t stream) {
   if (a.a_bytes >= (1L << 31) || a.b_bytes >= (1L << 31)) return hipErrorInvalidValue;
   a.tiles_n = (n_logical + BN - 1) / BN;
   auto kern = gemm_kernel<BM, BN, WM, WN, AKS, BKS, EPI>;
-  static bool attr_done = false;      // one flag per instantiation
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsLimitOnce lds_limit;      // one per instantiation
+  if (hipError_t e = lds_limit.ensure(reinterpret_cast<const void*>(kern), LDS); e != hipSuccess) return e;
   const int T = a.tiles_m * a.tiles_n;
   a.group_m = (T >= 16 && a.tiles_m >= 2) ? 2 : 0;    // measured: a third fewer L2 misses, 1-2 % on the layer
   hipLaunchKernelGGL(kern, dim3(a.group_m ? 8 * ((T + 7) / 8) : T), dim3(NT), LDS, stream, a);

@@ -150,7 +150,8 @@ template <int NT, int R, bool RMS, bool SUMS>
 __global__ __launch_bounds__(NT)
 void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
   constexpr int NW = NT / 64;
-  __shared__ __align__(16) float red[2][NW][2 * R];
+  constexpr int RW = 2 * R < 4 ? 4 : 2 * R;     // row sums per wave and iteration, padded to whole 16-byte reads
+  __shared__ __align__(16) float red[2][NW][RW];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nw = blockDim.x >> 6;
   const int nch = p.h >> 3;
@@ -214,15 +215,15 @@ void norm_bwd_kernel(const NormBwdArgs p, int rows_per_block) {
     }
     if (lane == 0) {
 #pragma unroll
-      for (int k = 0; k < 2 * R; ++k) red[buf][wave][k] = sums[k];
+      for (int k = 0; k < RW; ++k) red[buf][wave][k] = k < 2 * R ? sums[k] : 0.0f;
     }
     __syncthreads();
-    float tot[2 * R];
+    float tot[RW];
 #pragma unroll
-    for (int k = 0; k < 2 * R; ++k) tot[k] = 0.0f;
+    for (int k = 0; k < RW; ++k) tot[k] = 0.0f;
     for (int w = 0; w < nw; ++w) {
 #pragma unroll
-      for (int k4 = 0; k4 < 2 * R; k4 += 4) {
+      for (int k4 = 0; k4 < RW; k4 += 4) {
         const f32x4 t = *reinterpret_cast<const f32x4*>(&red[buf][w][k4]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) tot[k4 + e] += t[e];

@@ -31,9 +31,9 @@ EXPORTS = (
     "domino_stack_workspace_bytes", "domino_stack_fwd", "domino_stack_bwd",
     "domino_gemm", "domino_norm_fwd",
     "domino_norm_bwd_scratch_floats", "domino_norm_bwd", "domino_attention_fwd", "domino_attention_bwd",
-    "domino_rope", "domino_colsum", "domino_profile_enable", "domino_profile_classes",
+    "domino_rope", "domino_colsum", "domino_mfma_probe", "domino_profile_enable", "domino_profile_classes",
     "domino_profile_name", "domino_profile_read", "domino_profile_reset", "domino_profile_records",
-    "domino_profile_record", "domino_last_error",
+    "domino_profile_record", "domino_last_error", "domino_last_warning", "domino_capture_supported",
     "domino_version", "domino_shutdown",
 )
 
@@ -112,6 +112,7 @@ def load() -> C.CDLL:
         "domino_attention_bwd": (i32, [vp, i64, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]),
         "domino_rope": (i32, [vp, i64, i32, i32, i32, i32, i32, i32, f32, i32, vp]),
         "domino_colsum": (i32, [vp, i64, i32, i32, vp, i32, vp, vp]),
+        "domino_mfma_probe": (i32, [vp, vp, vp, i32, i32, C.POINTER(C.c_double), vp]),
         "domino_profile_enable": (i32, [i32]),
         "domino_profile_classes": (i32, []),
         "domino_profile_name": (C.c_char_p, [i32]),
@@ -120,6 +121,8 @@ def load() -> C.CDLL:
         "domino_profile_records": (i32, []),
         "domino_profile_record": (i32, [i32, C.POINTER(i32), C.POINTER(C.c_void_p), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "domino_last_error": (C.c_char_p, []),
+        "domino_last_warning": (C.c_char_p, []),
+        "domino_capture_supported": (i32, [i32, i32]),
         "domino_version": (C.c_char_p, []),
         "domino_shutdown": (None, []),
     }
@@ -195,6 +198,14 @@ def domino_saved_slot(cfg: domino_cfg, name: str):
 
 def domino_last_error() -> str:
     return load().domino_last_error().decode()
+
+
+def domino_last_warning() -> str:
+    return load().domino_last_warning().decode()
+
+
+def domino_capture_supported(nstreams: int, p: int) -> bool:
+    return bool(load().domino_capture_supported(nstreams, p))
 
 
 def domino_version() -> str:
@@ -320,6 +331,13 @@ def domino_rope(m, ld, rows, seq, col0, nblocks, heads, head_dim, base, inverse,
 
 def domino_colsum(g, ld, rows, n, out, accumulate, scratch, stream=None) -> None:
     _check(load().domino_colsum(_ptr(g), ld, rows, n, _ptr(out), int(accumulate), _ptr(scratch), _stream(stream)))
+
+
+def domino_mfma_probe(a, b, out, blocks, iters, stream=None) -> float:
+    """Enqueues the probe; returns the flops of the launch."""
+    fl = C.c_double()
+    _check(load().domino_mfma_probe(_ptr(a), _ptr(b), _ptr(out), blocks, iters, C.byref(fl), _stream(stream)))
+    return fl.value
 
 
 # --------------------------------------------------------------------------- instrumentation

@@ -33,8 +33,8 @@ def test_bench_prints_one_json_line_with_the_contract_keys():
     torch = pytest.importorskip("torch")
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    r = subprocess.run([sys.executable, BENCH, "--workload", "tiny", "--steps", "3", "--warmup", "1", "--stack-layers", "2"],
-                       capture_output=True, text=True, timeout=600, cwd=ROOT)
+    r = subprocess.run([sys.executable, BENCH, "--workload", "tiny", "--steps", "3", "--warmup", "1", "--stack-layers", "2",
+                        "--no-other-workloads"], capture_output=True, text=True, timeout=600, cwd=ROOT)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
     assert len(lines) == 1
@@ -47,10 +47,32 @@ def test_bench_prints_one_json_line_with_the_contract_keys():
     assert d["config"]["workload"] == "tiny" and "model" not in d["config"]
     assert d["value"] > 0 and d["ms_per_step"] > 0
     rf = d["roofline"]
-    for k in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+    for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_source"):
         assert k in rf, k
+    assert d["other_workloads"] is None
+    assert d["measured_mfma_ceiling"]["value"] > 500.0 and 0.0 < d["pct_of_measured_mfma_ceiling"] < 100.0
     assert rf["bound"] == "mfma" and rf["peak"] == 2500.0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-9
     cb = d["cpu_baseline"]
     for k in ("value", "unit", "cores", "kind", "sample"):
         assert k in cb, k
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1
+
+
+@pytest.mark.gpu
+def test_bench_graph_replay_mode_prints_its_line_with_a_roofline():
+    """--graph times replays of the captured step; the per-launch roofline pass runs the eager step beside it."""
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    r = subprocess.run([sys.executable, BENCH, "--workload", "tiny", "--steps", "3", "--warmup", "1", "--graph",
+                        "--no-other-workloads", "--no-cpu-baseline", "--no-ceiling"],
+                       capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([l for l in r.stdout.splitlines() if l.strip()][-1])
+    assert d["value"] > 0 and d["roofline"]["achieved"] > 0 and d["roofline"]["launches_per_step"] >= 1
+
+
+def test_bench_refuses_graph_capture_with_a_pool_the_library_does_not_capture():
+    r = subprocess.run([sys.executable, BENCH, "--workload", "tiny", "--graph", "--streams", "3"],
+                       capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert r.returncode == 2 and "--graph is limited" in r.stderr and not r.stdout.strip()

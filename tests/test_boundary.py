@@ -136,6 +136,23 @@ def test_single_kernel_entry_points_validate():
     assert lib.domino_profile_record(0, None, None, None, None) == domino.ERR_NULL_POINTER
 
 
+def test_capture_is_offered_for_the_pools_that_replay_bit_for_bit_only():
+    """Pools of 1, 2 or 4 streams of which 1, 2 or 4 carry slices; everything else is refused (3 and 8 have aborted)."""
+    ok = {(n, p) for n in range(1, 10) for p in range(1, 10) if domino.domino_capture_supported(n, p)}
+    want = {(n, p) for n in (1, 2, 4) for p in range(1, 10) if min(n, p) in (1, 2, 4)}
+    assert ok == want
+    assert not domino.domino_capture_supported(3, 4) and not domino.domino_capture_supported(8, 4)
+    assert not domino.domino_capture_supported(0, 4) and not domino.domino_capture_supported(4, 0)
+
+
+def test_no_warning_before_any_layer_call_and_probe_validates():
+    lib = domino.load()
+    assert domino.domino_last_warning() == ""
+    assert lib.domino_mfma_probe(None, 1, 1, 1, 1, None, None) == domino.ERR_NULL_POINTER
+    assert lib.domino_mfma_probe(1, 1, 1, 0, 1, None, None) == domino.ERR_INVALID_ARG
+    assert lib.domino_mfma_probe(1, 1, 1, 1, 0, None, None) == domino.ERR_INVALID_ARG
+
+
 def test_tuner_candidates_cut_exactly():
     from paper_2409_15241_amd import synth, tune
     sc = synth.WORKLOADS["gpt3-13b"]

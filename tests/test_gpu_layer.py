@@ -55,10 +55,15 @@ def oracle(sc, params, x, dy, others):
     return F, B
 
 
+LSE_ABS_TOL = 2e-2      # log-sum-exp of the scaled scores, absolute: the relative bar alone would allow 0.15 at 2048 keys
+
+
 def check(got, F, B, tol=TOL, grad_scale=1.0):
     worst = {}
     for k in ("attn_partial", "mlp_partial", "y", "x1", "ctx", "lse"):
         worst[k] = relerr(got[k], F[k])
+    lse_abs = float(np.max(np.abs(got["lse"] - F["lse"])))
+    assert lse_abs < LSE_ABS_TOL, f"max |lse error| {lse_abs:.3e} (absolute bar {LSE_ABS_TOL})"
     for k in ("dln2_partial", "dln1_partial", "dx"):
         worst[k] = relerr(got[k], B[k])
     for k, g in B["grads"].items():
@@ -71,12 +76,21 @@ def check(got, F, B, tol=TOL, grad_scale=1.0):
     return worst
 
 
+_ORACLE_CACHE = {}     # the last workload's inputs and oracle result: it does not depend on p, q or the pool
+
+
 def case(H, sc, random_affine=False, with_others=True, nstreams=4):
-    params = synth.make_rank_params(sc, random_affine=random_affine)
-    x, dy = synth.make_activations(sc)
-    others = synth.make_others(sc) if with_others else None
+    """One forward + backward through the C ABI against the oracle.  The oracle result depends on the shard, not on
+    the slicing, so consecutive cases that differ in (p, q, streams) only share one oracle run."""
+    key = (sc.replace(p=1, q=1), random_affine, with_others)
+    if key not in _ORACLE_CACHE:
+        _ORACLE_CACHE.clear()
+        params = synth.make_rank_params(sc, random_affine=random_affine)
+        x, dy = synth.make_activations(sc)
+        others = synth.make_others(sc) if with_others else None
+        _ORACLE_CACHE[key] = (params, x, dy, others) + oracle(sc, params, x, dy, others)
+    params, x, dy, others, F, B = _ORACLE_CACHE[key]
     got = run_gpu(H, sc, params, x, dy, others, nstreams)
-    F, B = oracle(sc, params, x, dy, others)
     return check(got, F, B)
 
 
@@ -148,7 +162,18 @@ def test_mid_shapes_with_ragged_tiles(H, sc):
     case(H, sc, random_affine=True)
 
 
-FULL = [synth.WORKLOADS[n] for n in ("gpt3-13b", "llama2-7b", "gpt3-30b", "gpt3-2.7b-s512-mb64", "llama2-13b-s512-mb16")]
+# head_dim 128 at hidden 8192: the widest rows the norm kernels take (1024 threads a row in the backward, with the
+# column sums of the two row-cut products' bias gradients)
+WIDE = synth.ShardConfig("wide-gpt-h8192", 8192, 64, 8, 3, 2, 2, 2, 136, 32768, synth.ARCH_GPT, index=14)
+
+
+def test_widest_hidden_size(H):
+    case(H, WIDE, random_affine=True)
+
+
+# the five configured shards (GPT-3 13B is the one bench.py times) and shards at the evaluation's own shapes
+FULL = [synth.WORKLOADS[n] for n in ("gpt3-13b", "gpt3-2.7b", "llama2-7b", "llama2-13b", "gpt3-30b", "gpt3-2.7b-s512-mb64",
+                                     "llama2-13b-s512-mb16")]
 
 
 @pytest.mark.parametrize("sc", FULL, ids=[m.name for m in FULL])
@@ -157,6 +182,17 @@ def test_full_size_shard_in_the_benchmark_configuration(H, sc):
     launches them: every output and gradient element against the oracle, which finishes a full-size
     layer in seconds."""
     case(H, sc, random_affine=True, nstreams=4)
+
+
+# Other slicings of full-size shards: the tile of every product is chosen from the rows of a slice and from the
+# number of slices in flight, so each (p, q, pool) runs other kernel instantiations than the configured one.
+SLICINGS = [("gpt3-13b", 1, 1, 1), ("gpt3-13b", 2, 4, 2), ("gpt3-13b", 4, 1, 4), ("gpt3-13b", 2, 2, 4),
+            ("llama2-7b", 1, 1, 1), ("llama2-7b", 2, 1, 2), ("llama2-7b", 1, 4, 4)]
+
+
+@pytest.mark.parametrize("name,p,q,nstreams", SLICINGS, ids=[f"{n}-p{p}q{q}-{k}streams" for n, p, q, k in SLICINGS])
+def test_full_size_shard_at_other_slicings(H, name, p, q, nstreams):
+    case(H, synth.WORKLOADS[name].replace(p=p, q=q), random_affine=True, nstreams=nstreams)
 
 
 def test_schedule_invariance_bitwise(H):
@@ -177,12 +213,16 @@ def test_schedule_invariance_bitwise(H):
             np.testing.assert_array_equal(g, c["grads"][k], err_msg=k)
 
 
-@pytest.mark.parametrize("nstreams", [2, 4])
-def test_repeated_steps_are_bitwise_identical(H, nstreams):
+# GeLU at head_dim 64, SwiGLU + rotary embedding at head_dim 128 (batch 4 so that two slices run side by side), and
+# head_dim 80
+REPEAT = [(MID[2], 2), (MID[2], 4), (MID[1].replace(batch=4, p=2), 2), (MID[0], 2)]
+
+
+@pytest.mark.parametrize("sc,nstreams", REPEAT, ids=[f"{c.name}-{k}streams" for c, k in REPEAT])
+def test_repeated_steps_are_bitwise_identical(H, sc, nstreams):
     """The same step on the same buffers, many times while other slices' kernels share the CUs: every
     repetition gives the bits of the first (no value may depend on the timing of a look-ahead read or
     of another stream)."""
-    sc = MID[2]
     params = synth.make_rank_params(sc, random_affine=True)
     x, dy = synth.make_activations(sc)
     buf = H.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=nstreams)
@@ -327,3 +367,80 @@ def test_graph_replay_is_bitwise_the_eager_step(H):
         other.forward()
         other.backward(accumulate=False)
         other.sync()
+
+
+def _hip_runtime():
+    """The HIP runtime this process already runs on (torch's), for the few calls the test below makes itself."""
+    import ctypes
+    with open("/proc/self/maps") as fh:
+        paths = {ln.split()[-1] for ln in fh if "libamdhip64" in ln}
+    assert len(paths) == 1, paths
+    return ctypes.CDLL(paths.pop())
+
+
+def test_capture_with_an_unsupported_pool_is_refused_before_anything_is_enqueued(H):
+    """streams[0] under capture with a pool of 3 streams: the call returns DOMINO_ERR_UNSUPPORTED and has enqueued
+    nothing, so the capture ends with an empty graph (which is destroyed, never instantiated)."""
+    import ctypes
+    from paper_2409_15241_amd import domino as D
+    sc = TINY.replace(batch=4, p=4, q=2)
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    buf = H.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=3)
+    buf.forward(); buf.backward(); buf.sync()                  # eager calls on 3 streams are fine
+    hip = _hip_runtime()
+    s0 = ctypes.c_void_p(buf.streams[0].cuda_stream)
+    assert hip.hipStreamBeginCapture(s0, 1) == 0              # thread-local capture mode
+    codes = []
+    try:
+        for fn in (buf.forward, buf.backward):
+            try:
+                fn()
+                codes.append(0)
+            except D.DominoError as e:
+                codes.append(e.code)
+    finally:
+        graph = ctypes.c_void_p()
+        rc = hip.hipStreamEndCapture(s0, ctypes.byref(graph))
+        nodes = ctypes.c_size_t(123)
+        if rc == 0 and graph:
+            hip.hipGraphGetNodes(graph, None, ctypes.byref(nodes))
+            hip.hipGraphDestroy(graph)
+    assert rc == 0 and codes == [D.ERR_UNSUPPORTED, D.ERR_UNSUPPORTED]
+    assert nodes.value == 0
+    buf.forward(); buf.backward(); buf.sync()                  # and the pool is usable afterwards
+
+
+@pytest.mark.parametrize("nstreams", [3, 8])
+@pytest.mark.skip(reason="instantiating a HIP graph captured with a pool of 3 or 8 streams aborted inside the runtime and the "
+                         "cause has not been shown from the host side: the library refuses such captures "
+                         "(test_capture_with_an_unsupported_pool_is_refused...) and the case stays off the GPU")
+def test_graph_replay_with_other_pools(H, nstreams):
+    sc = TINY.replace(batch=4, p=4, q=2)
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    buf = H.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=nstreams)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=buf.streams[0]):
+        buf.forward()
+        buf.backward(accumulate=False)
+    graph.replay()
+    buf.sync()
+
+
+def test_hardware_queue_note(H):
+    """Four slices on four streams with fewer hardware queues than streams + 1 configured: the library says so
+    once; with enough queues it stays silent."""
+    import os
+    from paper_2409_15241_amd import domino as D
+    sc = TINY.replace(batch=4, p=4, q=2)
+    params = synth.make_rank_params(sc, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    buf = H.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=4)
+    buf.forward(); buf.sync()
+    have = int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0)
+    note = D.domino_last_warning()
+    if have >= 5:
+        assert note == ""
+    else:
+        assert "GPU_MAX_HW_QUEUES" in note and ">= 5" in note
