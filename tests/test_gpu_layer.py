@@ -44,6 +44,11 @@ def run_gpu(H, sc, params, x, dy, others, nstreams=4, accumulate_twice=False):
     out["x1"] = H.to_host_f64(buf.saved_tensor("x1")).reshape(*shp, sc.hidden)
     out["ctx"] = H.to_host_f64(buf.saved_tensor("ctx")).reshape(*shp, sc.h_local)
     out["lse"] = buf.saved_tensor("lse").cpu().numpy().astype(np.float64).reshape(sc.batch, sc.local_heads, sc.seq)
+    # q, k, v as the attention kernel read them (bf16, after the rotary embedding), first and last batch element
+    qkv = buf.saved_tensor("qkv").view(sc.batch, sc.seq, 3, sc.local_heads, sc.head_dim)
+    picks = sorted({0, sc.batch - 1})
+    out["qkv_batches"] = picks
+    out["qkv"] = np.stack([H.to_host_f64(qkv[b]) for b in picks]).transpose(2, 0, 3, 1, 4)    # [3, b', heads, s, d]
     return out
 
 
@@ -55,15 +60,25 @@ def oracle(sc, params, x, dy, others):
     return F, B
 
 
-LSE_ABS_TOL = 2e-2      # log-sum-exp of the scaled scores, absolute: the relative bar alone would allow 0.15 at 2048 keys
+# The softmax statistics, absolute: against the whole-layer oracle the log-sum-exp carries the bf16 rounding of q and k
+# (an error that grows with the size of the scores), so the kernel's own statistics are held, at every size, against
+# the oracle's attention on exactly the q, k, v the kernel read: there only fp32 summation and the 2^x unit differ.
+LSE_ABS_TOL = 2e-3
 
 
 def check(got, F, B, tol=TOL, grad_scale=1.0):
     worst = {}
     for k in ("attn_partial", "mlp_partial", "y", "x1", "ctx", "lse"):
         worst[k] = relerr(got[k], F[k])
-    lse_abs = float(np.max(np.abs(got["lse"] - F["lse"])))
-    assert lse_abs < LSE_ABS_TOL, f"max |lse error| {lse_abs:.3e} (absolute bar {LSE_ABS_TOL})"
+    q, k_, v = got["qkv"]
+    ctx2, lse2 = O.attention_fwd(q, k_, v)
+    bsel = got["qkv_batches"]
+    lse_abs = float(np.max(np.abs(got["lse"][bsel] - lse2)))
+    assert lse_abs < LSE_ABS_TOL, f"max |lse error| {lse_abs:.3e} against attention on the kernel's own q, k, v (bar {LSE_ABS_TOL})"
+    b, s = got["ctx"].shape[:2]
+    ctx_gpu = got["ctx"].reshape(b, s, q.shape[1], q.shape[3])[bsel].transpose(0, 2, 1, 3)
+    worst["ctx_own_qkv"] = relerr(ctx_gpu, ctx2)
+    assert worst["ctx_own_qkv"] <= 1e-2, worst
     for k in ("dln2_partial", "dln1_partial", "dx"):
         worst[k] = relerr(got[k], B[k])
     for k, g in B["grads"].items():
