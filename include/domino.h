@@ -259,6 +259,15 @@ int domino_rope(void* m, int64_t ld, int rows, int seq, int col0, int nblocks, i
 int domino_colsum(const void* g, int64_t ld, int rows, int n, float* out, int accumulate,
                   float* scratch, void* stream);
 
+/* domino_colsum for callers that cannot allocate device memory and have no scratch to pass (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same two kernels, with the first stage's
+ * 64 x n partial sums in a 2 MiB array that is part of the library's device code (one copy on every GPU the library
+ * runs on, held until the process ends).  Allocates nothing.  n is limited to 8192 columns (DOMINO_ERR_UNSUPPORTED
+ * beyond); other arguments and errors as domino_colsum; results are bitwise those of domino_colsum.
+ * All calls on one GPU share the array: two calls whose kernels can overlap (different streams without an
+ * ordering between them, or different host threads' streams) race on it; calls on one stream are safe. */
+int domino_colsum_noalloc(const void* g, int64_t ld, int rows, int n, float* out, int accumulate, void* stream);
+
 /* MFMA-only probe for the "share of the measured matrix ceiling" figure that goes beside the share of the nominal
  * peak (the paper's metric is throughput, Sec. 5.2; a roofline needs the ceiling the chip really sustains): `blocks`
  * workgroups of 4 waves, every wave issuing iters x 8 independent 32x32x16 bf16 MFMAs back to back on one A and

@@ -947,6 +947,50 @@ int domino_colsum(const void* g, int64_t ld, int rows, int n, float* out, int ac
   return DOMINO_OK;
 }
 
+// ---- column sums without a scratch argument: for callers that cannot allocate -----------------------------------
+// The first stage's partial rows live in a file-scope device array.  In host code the array's name is only a
+// stand-in for the symbol: its device address is looked up once per device and only that address is handed to
+// the kernels.
+}  // extern "C"
+namespace {
+constexpr int COLSUM_STATIC_MAX_N = 8192;
+static __device__ __align__(256) float scratch[COLSUM_PARTS * COLSUM_STATIC_MAX_N];     // 2 MiB on every GPU used
+std::map<int, float*> g_scratch_ptr;       // per device: every GPU holds its own copy of the array at its own address
+
+int static_scratch(float** ptr) {          // g_mutex held
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+  auto it = g_scratch_ptr.find(dev);
+  if (it == g_scratch_ptr.end()) {
+    float* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (!p) return fail(DOMINO_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    it = g_scratch_ptr.emplace(dev, p).first;
+  }
+  *ptr = it->second;
+  return DOMINO_OK;
+}
+}  // namespace
+extern "C" {
+
+int domino_colsum_noalloc(const void* g, int64_t ld, int rows, int n, float* out, int accumulate, void* stream) {
+  if (!g || !out) return fail(DOMINO_ERR_NULL_POINTER, "g or out is NULL");
+  if (rows <= 0 || n <= 0) return fail(DOMINO_ERR_INVALID_ARG, "rows and n must be positive");
+  if (n % 8 || ld % 8 || ld < n) return fail(DOMINO_ERR_UNSUPPORTED, "n and ld must be multiples of 8, ld >= n");
+  if (n > COLSUM_STATIC_MAX_N)
+    return fail(DOMINO_ERR_UNSUPPORTED, "n = %d exceeds the %d columns the library's own scratch holds; use domino_colsum "
+                "with a scratch buffer of the caller's", n, COLSUM_STATIC_MAX_N);
+  std::lock_guard<std::mutex> lock(g_mutex);
+  float* part = nullptr;
+  TRY(static_scratch(&part));
+  hipStream_t st = as_stream(stream);
+  // the first stage writes every one of its COLSUM_PARTS x n partial sums (zeros for row ranges past the end), so
+  // nothing of an earlier call's contents is read and nothing has to be cleared
+  HIP_TRY(colsum_partial_launch(g, ld, rows, n, part, st), "colsum launch");
+  HIP_TRY(colsum_finish_launch(part, COLSUM_PARTS, n, out, accumulate, st), "colsum launch");
+  return DOMINO_OK;
+}
+
 int domino_mfma_probe(const void* a, const void* b, float* out, int blocks, int iters, double* flops, void* stream) {
   if (!a || !b || !out) return fail(DOMINO_ERR_NULL_POINTER, "a, b or out is NULL");
   if (blocks < 1 || blocks > 65536 || iters < 1 || iters > (1 << 24))

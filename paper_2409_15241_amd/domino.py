@@ -31,7 +31,7 @@ EXPORTS = (
     "domino_stack_workspace_bytes", "domino_stack_fwd", "domino_stack_bwd",
     "domino_gemm", "domino_norm_fwd",
     "domino_norm_bwd_scratch_floats", "domino_norm_bwd", "domino_attention_fwd", "domino_attention_bwd",
-    "domino_rope", "domino_colsum", "domino_mfma_probe", "domino_profile_enable", "domino_profile_classes",
+    "domino_rope", "domino_colsum", "domino_colsum_noalloc", "domino_mfma_probe", "domino_profile_enable", "domino_profile_classes",
     "domino_profile_name", "domino_profile_read", "domino_profile_reset", "domino_profile_records",
     "domino_profile_record", "domino_last_error", "domino_last_warning", "domino_capture_supported",
     "domino_version", "domino_shutdown",
@@ -112,6 +112,7 @@ def load() -> C.CDLL:
         "domino_attention_bwd": (i32, [vp, i64, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]),
         "domino_rope": (i32, [vp, i64, i32, i32, i32, i32, i32, i32, f32, i32, vp]),
         "domino_colsum": (i32, [vp, i64, i32, i32, vp, i32, vp, vp]),
+        "domino_colsum_noalloc": (i32, [vp, i64, i32, i32, vp, i32, vp]),
         "domino_mfma_probe": (i32, [vp, vp, vp, i32, i32, C.POINTER(C.c_double), vp]),
         "domino_profile_enable": (i32, [i32]),
         "domino_profile_classes": (i32, []),
@@ -331,6 +332,10 @@ def domino_rope(m, ld, rows, seq, col0, nblocks, heads, head_dim, base, inverse,
 
 def domino_colsum(g, ld, rows, n, out, accumulate, scratch, stream=None) -> None:
     _check(load().domino_colsum(_ptr(g), ld, rows, n, _ptr(out), int(accumulate), _ptr(scratch), _stream(stream)))
+
+
+def domino_colsum_noalloc(g, ld, rows, n, out, accumulate, stream=None) -> None:
+    _check(load().domino_colsum_noalloc(_ptr(g), ld, rows, n, _ptr(out), int(accumulate), _stream(stream)))
 
 
 def domino_mfma_probe(a, b, out, blocks, iters, stream=None) -> float:
