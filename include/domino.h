@@ -220,6 +220,14 @@ int domino_gemm(int layout, int epilogue, int tile,
                 int M, int N, int K, const void* bias, void* aux, int64_t ldaux,
                 int n_split, int beta, int gelu_tanh, void* stream);
 
+/* The forward product C[M,N] = A[M,K] * B[K,N] (bf16, no bias) with the rotary embedding (Sec. 5.4 names it for the
+ * Llama-2 models) applied in the epilogue: N is a row of heads of head_dim (64 or 128) columns; in the heads that
+ * start below column rope_cols the pairs (i, i + head_dim/2) turn by pos * base^(-2i/head_dim), pos = row % seq;
+ * the other heads are stored as they are.  This is how the block's QKV product hands q and k to the attention
+ * (rope_cols = 2 * heads * head_dim).  tile as in domino_gemm. */
+int domino_gemm_rope(int tile, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                     int M, int N, int K, int seq, int head_dim, int rope_cols, float base, void* stream);
+
 /* y = Norm(x + add1 + add2 + vec): LayerNorm (rms = 0) or RMSNorm (rms = 1) over the last axis of
  * [rows, h]; add1, add2 [rows, h], vec [h], beta [h], xsum (out: the pre-norm sum), mean may be NULL.
  * mean, rstd: fp32 [rows].  h must be a multiple of 8 and at most 8192. */
@@ -246,6 +254,12 @@ int domino_attention_fwd(const void* qkv, int64_t ld, int batch, int seq, int he
 /* Gradients of the above: dqkv (same layout as qkv) from dctx.  dot: fp32 scratch [batch, heads, seq]. */
 int domino_attention_bwd(const void* qkv, int64_t ld, const void* ctx, const void* dctx, const float* lse,
                          void* dqkv, float* dot, int batch, int seq, int heads, int head_dim, void* stream);
+
+/* domino_attention_bwd for q and k that carry the rotary embedding (as domino_gemm_rope or domino_rope leaves them):
+ * the dq and dk columns of dqkv are the gradients with respect to q and k BEFORE the rotation (the transposed rotation
+ * is applied where they are stored); dv as before.  head_dim in {64, 80, 128}. */
+int domino_attention_bwd_rope(const void* qkv, int64_t ld, const void* ctx, const void* dctx, const float* lse,
+                              void* dqkv, float* dot, int batch, int seq, int heads, int head_dim, float base, void* stream);
 
 /* Rotary embedding in place on nblocks consecutive [heads*head_dim]-wide column blocks of
  * m[rows, ld] starting at column col0 (pairs (i, i + d/2), angle pos * base^(-2i/d), pos = row % seq);

@@ -298,6 +298,10 @@ int check_params(const Layout& L, const domino_params* P) {
 }
 
 
+// The QKV product applies the rotary embedding in its epilogue when a head's partner columns (i, i + d/2) can meet in
+// one lane there: heads of 64 or 128 columns.  Other head sizes (80) take a separate in-place pass over q and k.
+inline bool rope_fused(const Layout& L) { return L.llama && (L.d == 64 || L.d == 128); }
+
 // ---------------------------------------------------------------------------------- the piece schedule
 // One block's buffers as the forward / the backward sees them (all device pointers, caller-owned).
 struct FwdLayer {
@@ -408,9 +412,14 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
     ProfScope ps(PC_GEMM_QKV, st);
     GemmArgs a = gemm_args(ln1, L.h, P->w_qkv, 3 * L.hl, qkv, 3 * L.hl, Ms, 3 * L.hl, L.h);
     a.bias = P->b_qkv;
-    LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "qkv product");
+    if (rope_fused(L)) {     // q and k leave the product already rotated (the rotary embedding of Sec. 5.4)
+      a.rope_d = L.d; a.rope_seq = L.s; a.rope_cols = 2 * L.hl; a.rope_log2_base = log2f(cfg->rope_base);
+      LAUNCH(gemm_launch(GEMM_NN, EPI_ROPE, a, -1, st), "qkv product");
+    } else {
+      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "qkv product");
+    }
   }
-  if (L.llama) {
+  if (L.llama && !rope_fused(L)) {
     ProfScope ps(PC_ROPE, st);
     LAUNCH(rope_launch(qkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 0, st), "rotary embedding");
   }
@@ -574,11 +583,8 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     a.qkv = qkv; a.ld = 3 * L.hl; a.ctx = const_cast<char*>(ctx); a.ld_ctx = L.hl; a.dctx = dctx;
     a.lse = const_cast<float*>(lse); a.dot = dot; a.dqkv = dqkv;
     a.batch = L.b / L.p; a.seq = L.s; a.heads = L.nl; a.head_dim = L.d; a.scale = 1.0f / sqrtf((float)L.d);
+    a.rope = L.llama ? 1 : 0; a.rope_log2_base = log2f(cfg->rope_base);   // dq, dk are turned back where they are stored
     LAUNCH(attention_bwd_launch(a, st), "attention backward");
-  }
-  if (L.llama) {
-    ProfScope ps(PC_ROPE, st);
-    LAUNCH(rope_launch(dqkv, 3 * L.hl, Ms, L.s, 0, 2, L.nl, L.d, cfg->rope_base, 1, st), "rotary embedding backward");
   }
   {  // B8: input gradient of QKV: the tensor the fourth all-reduce would sum
     ProfScope ps(PC_DGRAD_QKV, st);
@@ -855,6 +861,23 @@ int domino_gemm(int layout, int epilogue, int tile,
   return DOMINO_OK;
 }
 
+int domino_gemm_rope(int tile, const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                     int M, int N, int K, int seq, int head_dim, int rope_cols, float base, void* stream) {
+  if (!A || !B || !C) return fail(DOMINO_ERR_NULL_POINTER, "A, B or C is NULL");
+  if (M <= 0 || N <= 0 || K <= 0 || seq <= 0) return fail(DOMINO_ERR_INVALID_ARG, "M, N, K, seq must be positive");
+  if (M % 8 || N % 8 || K % 8 || lda % 8 || ldb % 8 || ldc % 8) return fail(DOMINO_ERR_UNSUPPORTED, "dimensions must be multiples of 8");
+  if (tile < -1 || tile > 3) return fail(DOMINO_ERR_INVALID_ARG, "tile %d outside [-1, 3]", tile);
+  if (head_dim != 64 && head_dim != 128) return fail(DOMINO_ERR_UNSUPPORTED, "the rotary epilogue takes heads of 64 or 128 columns, not %d", head_dim);
+  if (N % head_dim || rope_cols < 0 || rope_cols > N || rope_cols % head_dim)
+    return fail(DOMINO_ERR_INVALID_ARG, "N and rope_cols must be multiples of head_dim, rope_cols <= N");
+  if (!(base > 1.0f)) return fail(DOMINO_ERR_INVALID_ARG, "base must exceed 1");
+  if (((long)(M - 1) * lda + K) * 2 >= TWO_GIB || ((long)(K - 1) * ldb + N) * 2 >= TWO_GIB) return fail(DOMINO_ERR_UNSUPPORTED, "an operand would reach 2 GiB");
+  GemmArgs a = gemm_args(A, lda, B, ldb, C, ldc, M, N, K);
+  a.rope_d = head_dim; a.rope_seq = seq; a.rope_cols = rope_cols; a.rope_log2_base = log2f(base);
+  HIP_TRY(gemm_launch(GEMM_NN, EPI_ROPE, a, tile, as_stream(stream)), "gemm launch");
+  return DOMINO_OK;
+}
+
 int domino_norm_fwd(const void* x, const void* add1, const void* add2, const void* vec,
                     const void* gamma, const void* beta, void* xsum, void* y, float* mean, float* rstd,
                     int rows, int h, int rms, float eps, void* stream) {
@@ -921,6 +944,20 @@ int domino_attention_bwd(const void* qkv, int64_t ld, const void* ctx, const voi
   a.qkv = qkv; a.ld = ld; a.ctx = const_cast<void*>(ctx); a.ld_ctx = (long)heads * head_dim; a.dctx = dctx;
   a.lse = const_cast<float*>(lse); a.dot = dot; a.dqkv = dqkv;
   a.batch = batch; a.seq = seq; a.heads = heads; a.head_dim = head_dim; a.scale = 1.0f / sqrtf((float)head_dim);
+  HIP_TRY(attention_bwd_launch(a, as_stream(stream)), "attention backward launch");
+  return DOMINO_OK;
+}
+
+int domino_attention_bwd_rope(const void* qkv, int64_t ld, const void* ctx, const void* dctx, const float* lse,
+                              void* dqkv, float* dot, int batch, int seq, int heads, int head_dim, float base, void* stream) {
+  if (!qkv || !ctx || !dctx || !lse || !dqkv || !dot) return fail(DOMINO_ERR_NULL_POINTER, "a required pointer is NULL");
+  TRY(check_attn(ld, batch, seq, heads, head_dim));
+  if (!(base > 1.0f)) return fail(DOMINO_ERR_INVALID_ARG, "base must exceed 1");
+  AttnArgs a{};
+  a.qkv = qkv; a.ld = ld; a.ctx = const_cast<void*>(ctx); a.ld_ctx = (long)heads * head_dim; a.dctx = dctx;
+  a.lse = const_cast<float*>(lse); a.dot = dot; a.dqkv = dqkv;
+  a.batch = batch; a.seq = seq; a.heads = heads; a.head_dim = head_dim; a.scale = 1.0f / sqrtf((float)head_dim);
+  a.rope = 1; a.rope_log2_base = log2f(base);
   HIP_TRY(attention_bwd_launch(a, as_stream(stream)), "attention backward launch");
   return DOMINO_OK;
 }

@@ -13,6 +13,8 @@ struct AttnArgs {
   void* dqkv;          // bf16 [batch*seq, ld] (backward output)
   int batch, seq, heads, head_dim;
   float scale;         // 1 / sqrt(head_dim)
+  int rope;            // backward: q and k of qkv carry the rotary embedding; dq and dk are turned back before the store
+  float rope_log2_base;
 };
 
 hipError_t attention_fwd_launch(const AttnArgs& a, hipStream_t st);

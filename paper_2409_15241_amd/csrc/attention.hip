@@ -69,6 +69,32 @@ DEV void store_transposed(const f32x16 (&o)[Dims<D>::DT], float scale, bf16_t* _
     }
 }
 
+// The rotary embedding's transpose on out^T[d, pos]: the gradient with respect to a rotated q or k, taken back to
+// the vector before the rotation.  The pair (i, i + D/2) of a position sits in one lane (accumulator rows 32 dt + 8 g
+// + 4 fh + e: adding D/2 = 32, 40 or 64 changes dt and g only), so nothing crosses lanes.
+template <int D>
+DEV void rope_back(f32x16 (&o)[Dims<D>::DT], int pos, int fh, float log2_base) {
+  constexpr int H = D / 2;
+  const float fpos = (float)pos;
+#pragma unroll
+  for (int dt = 0; dt < Dims<D>::DT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int dd0 = 32 * dt + 8 * g;               // this lane's rows of the group: dd0 + 4 fh + e
+      if (dd0 < H) {
+        const int dt2 = (dd0 + H) / 32, g2 = ((dd0 + H) % 32) / 8;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float sn, cs;
+          rope_sincos(fpos, rope_freq(dd0 + 4 * fh + e, D, log2_base), &sn, &cs);
+          const float lo = o[dt][4 * g + e], hi = o[dt2][4 * g2 + e];
+          o[dt][4 * g + e] = lo * cs + hi * sn;
+          o[dt2][4 * g2 + e] = hi * cs - lo * sn;
+        }
+      }
+    }
+}
+
 // ------------------------------------------------------------------------------------- forward
 // compile-time loop: f(std::integral_constant<int, I>) for I in [0, N)
 template <int I, int N, class F>
@@ -520,6 +546,7 @@ DEV void attn_bwd_dq_body(const AttnArgs& p, uint8_t* smem, int qb, int hh, int 
   }
   if (qpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + qpos) * ld + hh * D;
+    if (p.rope) rope_back<D>(dq, qpos, fh, p.rope_log2_base);
     store_transposed<D>(dq, p.scale, out, fh);
   }
 }
@@ -630,6 +657,7 @@ DEV void attn_bwd_dkv_body(const AttnArgs& p, uint8_t* smem, int kb, int hh, int
   }
   if (kpos < s) {
     bf16_t* out = static_cast<bf16_t*>(p.dqkv) + ((long)bi * s + kpos) * ld + hh * D;
+    if (p.rope) rope_back<D>(dk, kpos, fh, p.rope_log2_base);
     store_transposed<D>(dk, p.scale, out + hl, fh);
     store_transposed<D>(dv, 1.0f, out + 2 * hl, fh);
   }

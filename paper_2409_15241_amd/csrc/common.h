@@ -51,6 +51,18 @@ DEV float gelu_grad_f(float x, bool tanh_form) {
 }
 DEV float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
 
+// Rotary embedding (Sec. 5.4 names it for Llama-2): the pair (i, i + d/2) of a head at sequence position pos turns by
+// the angle pos * base^(-2 i / d).
+DEV float rope_freq(int i, int d, float log2_base) { return exp2f(-2.0f * (float)i / (float)d * log2_base); }
+// sin and cos of pos * freq on the hardware's sine / cosine units, which take their argument in revolutions: the angle
+// is reduced to its fractional number of turns first (at 4096 positions fp32 leaves about 5e-4 rad of it, a sixteenth
+// of what rounding the rotated value to bf16 costs).
+DEV void rope_sincos(float pos, float freq, float* sn, float* cs) {
+  const float turns = __builtin_amdgcn_fractf(pos * freq * 0.15915494309189535f);
+  *sn = __builtin_amdgcn_sinf(turns);
+  *cs = __builtin_amdgcn_cosf(turns);
+}
+
 // wave64 reductions over all lanes, on the VALU's data-parallel primitives (no LDS traffic): swaps inside quads,
 // rotations inside the rows of 16 lanes, then the two row broadcasts leave the total in lane 63, which is read
 // back as a wave-uniform value.  The order of the additions is fixed.

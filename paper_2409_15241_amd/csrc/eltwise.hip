@@ -18,8 +18,7 @@ void rope_kernel(bf16_t* __restrict__ m, long ld, int rows, int seq, int col0, i
   float sn[8], cs[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const float freq = exp2f(-2.0f * (float)(i0 + e) / (float)d * log2_base);
-    sincosf(pos * freq, &sn[e], &cs[e]);
+    sincosf(pos * rope_freq(i0 + e, d, log2_base), &sn[e], &cs[e]);
     if (inverse) sn[e] = -sn[e];
   }
   bf16_t* r = m + (long)row * ld + col0 + i0;

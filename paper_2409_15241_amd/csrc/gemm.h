@@ -11,6 +11,7 @@ enum GemmEpilogue {
   EPI_DGELU = 3,      // C = bf16(acc * GeLU'(aux))
   EPI_DSWIGLU = 4,    // C[:, n] = acc * up * silu'(gate); C[:, n_split + n] = acc * silu(gate)
   EPI_ACC_F32 = 5,    // C(fp32) = acc (+ C if beta)
+  EPI_ROPE = 6,       // C = bf16(acc) with the rotary embedding applied to columns below rope_cols (heads of rope_d columns)
 };
 enum GemmTile { GEMM_TILE_128x128 = 0, GEMM_TILE_256x128 = 1, GEMM_TILE_256x256 = 2, GEMM_TILE_128x256 = 3 };
 
@@ -22,6 +23,8 @@ struct GemmArgs {
   void* aux; long ldaux; // epilogue side tensor (read or written, see GemmEpilogue)
   int n_split;           // SwiGLU: number of gate (= up) columns
   int beta;              // EPI_ACC_F32: 1 = accumulate into C
+  int rope_d, rope_seq, rope_cols;   // EPI_ROPE: head width (64 or 128), sequence length (position = row % seq), rotated columns
+  float rope_log2_base;
   int gelu_tanh;
   int concurrency;       // launches of similar size expected in flight at once (other streams); 0 = 1
   int tiles_m, tiles_n;  // filled by the launcher

@@ -72,12 +72,24 @@ void gemm_kernel(const GemmArgs p) {
     }
   };
 
+  // Rotary embedding: the partner columns (i, i + d/2) of a head must meet in one lane of the epilogue, which pairs
+  // tile columns 32 apart inside a wave's 64 columns (as for SwiGLU).  Heads of 64 columns already lie that way; for
+  // heads of 128 the tile's second and third group of 32 inside every 128 trade places.
+  struct RopeCols {
+    int n0, n_end, d;
+    DEV int perm(int r) const {
+      return d == 128 ? ((r & ~96) | (((r >> 5) & 1) << 6) | (((r >> 6) & 1) << 5)) : r;
+    }
+    DEV int operator()(int r) const { const int g = n0 + perm(r); return g < n_end ? g : -1; }
+  };
+
   DmaLoader<BM, NW, AKS> ldA;
   DmaLoader<BN, NW, BKS> ldB;
   if constexpr (AKS) ldA.init_ks((int)p.lda, IdentityCols{m0, p.M}, wave, lane);
   else ldA.init_kc((int)p.lda, m0, p.M, wave, lane);
   if constexpr (BKS) {
     if constexpr (EPI == EPI_SWIGLU) ldB.init_ks((int)p.ldb, GluCols{tn * (BN / 2), p.n_split}, wave, lane);
+    else if constexpr (EPI == EPI_ROPE) ldB.init_ks((int)p.ldb, RopeCols{n0, p.N, p.rope_d}, wave, lane);
     else ldB.init_ks((int)p.ldb, IdentityCols{n0, p.N}, wave, lane);
   } else {
     ldB.init_kc((int)p.ldb, n0, p.N, wave, lane);
@@ -215,9 +227,21 @@ void gemm_kernel(const GemmArgs p) {
     col = tn * (BN / 2) + ((nl >> 6) << 5) + (nl & 31);
     n = col;
     n_ok = !((nl >> 5) & 1) && col < p.n_split;  // up groups are handled by the lane holding their gate group
+  } else if constexpr (EPI == EPI_ROPE) {
+    static_assert(EPI != EPI_ROPE || WN == 64, "the rotary epilogue pairs columns inside 64-column wave blocks");
+    n = n0 + RopeCols{n0, p.N, p.rope_d}.perm(nl);            // memory column of the first element of the pair
+    n_ok = !((nl >> 5) & 1) && n < p.N;                        // the partner groups are handled by the lane holding i
   } else {
     n = n0 + nl;
     n_ok = n < p.N;
+  }
+  // rotary embedding: the frequencies of this lane's 4 pair indices
+  [[maybe_unused]] float rfreq[4];
+  [[maybe_unused]] bool rot = false;
+  if constexpr (EPI == EPI_ROPE) {
+    rot = n_ok && n < p.rope_cols;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rfreq[e] = rot ? rope_freq(n % p.rope_d + e, p.rope_d, p.rope_log2_base) : 0.0f;
   }
   f32x4 bias4 = {0.0f, 0.0f, 0.0f, 0.0f};
   if constexpr (EPI == EPI_STORE || EPI == EPI_BIAS_GELU) {
@@ -238,7 +262,7 @@ void gemm_kernel(const GemmArgs p) {
       }
     // phase 1: every load of the block (LDS read-back and side tensors) is issued before any is used; rows or
     // columns outside the matrix read a safe address instead of branching, their results are never stored
-    f32x4 v[NT_ROWS], u[EPI == EPI_SWIGLU ? NT_ROWS : 1], old[EPI == EPI_ACC_F32 ? NT_ROWS : 1];
+    f32x4 v[NT_ROWS], u[(EPI == EPI_SWIGLU || EPI == EPI_ROPE) ? NT_ROWS : 1], old[EPI == EPI_ACC_F32 ? NT_ROWS : 1];
     u32x2 sa[(EPI == EPI_DGELU || EPI == EPI_DSWIGLU) ? NT_ROWS : 1], sb[EPI == EPI_DSWIGLU ? NT_ROWS : 1];
     bool ok[NT_ROWS];
     long mrow[NT_ROWS];
@@ -249,7 +273,7 @@ void gemm_kernel(const GemmArgs p) {
       ok[t] = n_ok && m < p.M;
       mrow[t] = ok[t] ? (long)m : 0L;
       v[t] = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + rcol * 4);
-      if constexpr (EPI == EPI_SWIGLU) u[t] = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + ((rcol + 32) % WN) * 4);
+      if constexpr (EPI == EPI_SWIGLU || EPI == EPI_ROPE) u[t] = *reinterpret_cast<const f32x4*>(wbuf + row * ROWB + ((rcol + 32) % WN) * 4);
       const int ns = ok[t] ? n : 0;
       if constexpr (EPI == EPI_ACC_F32) {
         if (p.beta) old[t] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(p.C) + mrow[t] * p.ldc + ns);
@@ -281,6 +305,26 @@ void gemm_kernel(const GemmArgs p) {
       } else if constexpr (EPI == EPI_ACC_F32) {
         if (p.beta) w += old[t];
         if (ok[t]) *reinterpret_cast<f32x4*>(static_cast<float*>(p.C) + mrow[t] * p.ldc + n) = w;
+      } else if constexpr (EPI == EPI_ROPE) {
+        f32x4 hi = u[t];
+        if (rot) {
+          const float pos = (float)(int)(mrow[t] % p.rope_seq);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float sn, cs;
+            rope_sincos(pos, rfreq[e], &sn, &cs);
+            const float a = w[e], b = hi[e];
+            w[e] = a * cs - b * sn;
+            hi[e] = b * cs + a * sn;
+          }
+        }
+        if (ok[t]) {
+          bf16_t* crow = static_cast<bf16_t*>(p.C) + mrow[t] * p.ldc + n;
+          const u32x2 plo = {pack_bf16(w[0], w[1]), pack_bf16(w[2], w[3])};
+          const u32x2 phi = {pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3])};
+          *reinterpret_cast<u32x2*>(crow) = plo;
+          *reinterpret_cast<u32x2*>(crow + (p.rope_d >> 1)) = phi;
+        }
       } else {
         w += bias4;
         if constexpr (EPI == EPI_BIAS_GELU) {
@@ -333,11 +377,20 @@ hipError_t launch_cfg(const GemmArgs& a0, hipStream_t stream) {
 
 template <bool AKS, bool BKS, int EPI>
 hipError_t launch_layout(const GemmArgs& a, int tile_cfg, hipStream_t stream) {
-  switch (tile_cfg) {
-    case GEMM_TILE_256x256: return launch_cfg<256, 256, 128, 64, AKS, BKS, EPI>(a, stream);
-    case GEMM_TILE_256x128: return launch_cfg<256, 128, 128, 64, AKS, BKS, EPI>(a, stream);
-    case GEMM_TILE_128x256: return launch_cfg<128, 256, 64, 128, AKS, BKS, EPI>(a, stream);
-    default:                return launch_cfg<128, 128, 64, 64, AKS, BKS, EPI>(a, stream);
+  if constexpr (EPI == EPI_ROPE) {          // needs 64-column wave blocks: the 128x256 tile has 128
+    if (tile_cfg == GEMM_TILE_128x256) tile_cfg = GEMM_TILE_256x256;
+    switch (tile_cfg) {
+      case GEMM_TILE_256x256: return launch_cfg<256, 256, 128, 64, AKS, BKS, EPI>(a, stream);
+      case GEMM_TILE_256x128: return launch_cfg<256, 128, 128, 64, AKS, BKS, EPI>(a, stream);
+      default:                return launch_cfg<128, 128, 64, 64, AKS, BKS, EPI>(a, stream);
+    }
+  } else {
+    switch (tile_cfg) {
+      case GEMM_TILE_256x256: return launch_cfg<256, 256, 128, 64, AKS, BKS, EPI>(a, stream);
+      case GEMM_TILE_256x128: return launch_cfg<256, 128, 128, 64, AKS, BKS, EPI>(a, stream);
+      case GEMM_TILE_128x256: return launch_cfg<128, 256, 64, 128, AKS, BKS, EPI>(a, stream);
+      default:                return launch_cfg<128, 128, 64, 64, AKS, BKS, EPI>(a, stream);
+    }
   }
 }
 
@@ -388,6 +441,7 @@ hipError_t gemm_launch(int layout, int epi, const GemmArgs& a, int tile_cfg, hip
       case EPI_STORE:     return launch_layout<false, true, EPI_STORE>(a, tile_cfg, stream);
       case EPI_BIAS_GELU: return launch_layout<false, true, EPI_BIAS_GELU>(a, tile_cfg, stream);
       case EPI_SWIGLU:    return launch_layout<false, true, EPI_SWIGLU>(a, tile_cfg, stream);
+      case EPI_ROPE:      return launch_layout<false, true, EPI_ROPE>(a, tile_cfg, stream);
       default: return hipErrorInvalidValue;
     }
   } else if (layout == GEMM_NT) {

@@ -29,7 +29,7 @@ EXPORTS = (
     "domino_validate_cfg", "domino_saved_bytes", "domino_workspace_bytes", "domino_saved_slot",
     "domino_layer_fwd", "domino_layer_bwd", "domino_layer_fwd_parts", "domino_layer_bwd_parts",
     "domino_stack_workspace_bytes", "domino_stack_fwd", "domino_stack_bwd",
-    "domino_gemm", "domino_norm_fwd",
+    "domino_gemm", "domino_gemm_rope", "domino_attention_bwd_rope", "domino_norm_fwd",
     "domino_norm_bwd_scratch_floats", "domino_norm_bwd", "domino_attention_fwd", "domino_attention_bwd",
     "domino_rope", "domino_colsum", "domino_colsum_noalloc", "domino_mfma_probe", "domino_profile_enable", "domino_profile_classes",
     "domino_profile_name", "domino_profile_read", "domino_profile_reset", "domino_profile_records",
@@ -105,6 +105,8 @@ def load() -> C.CDLL:
         "domino_stack_bwd": (i32, [cfgp, i32, C.POINTER(domino_params), vp, C.POINTER(domino_stack_bwd_io), vp,
                                    C.POINTER(domino_grads), i32, vp, sz, C.POINTER(vp), i32]),
         "domino_gemm": (i32, [i32, i32, i32, vp, i64, vp, i64, vp, i64, i32, i32, i32, vp, vp, i64, i32, i32, i32, vp]),
+        "domino_gemm_rope": (i32, [i32, vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, i32, f32, vp]),
+        "domino_attention_bwd_rope": (i32, [vp, i64, vp, vp, vp, vp, vp, i32, i32, i32, i32, f32, vp]),
         "domino_norm_fwd": (i32, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]),
         "domino_norm_bwd_scratch_floats": (sz, [i32, i32]),
         "domino_norm_bwd": (i32, [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp]),
@@ -298,6 +300,16 @@ def domino_gemm(layout, epilogue, tile, A, lda, B, ldb, Cmat, ldc, M, N, K, bias
                 n_split=0, beta=0, gelu_tanh=1, stream=None) -> None:
     _check(load().domino_gemm(layout, epilogue, tile, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat), ldc, M, N, K,
                               _ptr(bias), _ptr(aux), ldaux, n_split, beta, gelu_tanh, _stream(stream)))
+
+
+def domino_gemm_rope(tile, A, lda, B, ldb, Cmat, ldc, M, N, K, seq, head_dim, rope_cols, base, stream=None) -> None:
+    _check(load().domino_gemm_rope(tile, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat), ldc, M, N, K, seq, head_dim, rope_cols,
+                                   base, _stream(stream)))
+
+
+def domino_attention_bwd_rope(qkv, ld, ctx, dctx, lse, dqkv, dot, batch, seq, heads, head_dim, base, stream=None) -> None:
+    _check(load().domino_attention_bwd_rope(_ptr(qkv), ld, _ptr(ctx), _ptr(dctx), _ptr(lse), _ptr(dqkv), _ptr(dot),
+                                            batch, seq, heads, head_dim, base, _stream(stream)))
 
 
 def domino_norm_fwd(x, add1, add2, vec, gamma, beta, xsum, y, mean, rstd, rows, h, rms, eps, stream=None) -> None:

@@ -286,6 +286,71 @@ def test_rope(dom, inverse):
     np.testing.assert_array_equal(got[:, 2 * hl:], m[:, 2 * hl:])       # the v block is untouched
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("d,nh,b,s", [(128, 3, 2, 200), (64, 5, 3, 72), (128, 5, 1, 264)])
+def test_gemm_rope_epilogue(dom, tile, d, nh, b, s):
+    """The QKV product with the rotary embedding in its epilogue against the plain product followed by the oracle's
+    rotation: q and k heads turned, v heads untouched, positions wrapping at every sequence end inside a tile."""
+    rng = np.random.default_rng(100 * d + nh + tile)
+    hl = nh * d
+    M, N, K = b * s, 3 * hl, 136
+    A, B = rnd(rng, (M, K)), rnd(rng, (K, N), 0.1)
+    Cd = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    dom.domino_gemm_rope(tile, dev(A), K, dev(B), N, Cd, N, M, N, K, s, d, 2 * hl, 10000.0)
+    torch.cuda.synchronize()
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    cos, sin = O.rope_tables(s, d, 10000.0)
+    for blk in range(2):
+        part = ref[:, blk * hl:(blk + 1) * hl].reshape(b, s, nh, d).transpose(0, 2, 1, 3)
+        ref[:, blk * hl:(blk + 1) * hl] = O.rope_apply(part, cos, sin).transpose(0, 2, 1, 3).reshape(M, hl)
+    got = host(Cd)
+    for blk in range(3):
+        assert relerr(got[:, blk * hl:(blk + 1) * hl], ref[:, blk * hl:(blk + 1) * hl]) < BF16_OUT, blk
+
+
+def test_gemm_rope_epilogue_long_sequence(dom):
+    """4096 positions: the angle recurrence of the epilogue runs over every row of a tile without drifting."""
+    rng = np.random.default_rng(5)
+    d, nh, s, K = 128, 2, 4096, 72
+    hl = nh * d
+    A, B = rnd(rng, (s, K)), rnd(rng, (K, 3 * hl), 0.1)
+    Cd = torch.zeros((s, 3 * hl), dtype=torch.bfloat16, device="cuda")
+    dom.domino_gemm_rope(-1, dev(A), K, dev(B), 3 * hl, Cd, 3 * hl, s, 3 * hl, K, s, d, 2 * hl, 10000.0)
+    torch.cuda.synchronize()
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    cos, sin = O.rope_tables(s, d, 10000.0)
+    for blk in range(2):
+        part = ref[:, blk * hl:(blk + 1) * hl].reshape(1, s, nh, d).transpose(0, 2, 1, 3)
+        ref[:, blk * hl:(blk + 1) * hl] = O.rope_apply(part, cos, sin).transpose(0, 2, 1, 3).reshape(s, hl)
+    assert relerr(host(Cd), ref) < BF16_OUT
+
+
+@pytest.mark.parametrize("d,b,s,nh", [(64, 2, 200, 2), (80, 1, 136, 3), (128, 2, 264, 2)])
+def test_attention_backward_through_the_rotary_embedding(dom, d, b, s, nh):
+    """dq, dk with respect to q, k before the rotation: the oracle's attention gradients taken through its rotation."""
+    rng = np.random.default_rng(d + s + 7)
+    hl = nh * d
+    qkv, q, k, v = _attn_inputs(rng, b, s, nh, d)          # q, k here are the rotated vectors the kernel reads
+    dctx = rnd(rng, (b * s, hl))
+    ctx = torch.zeros((b * s, hl), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((b, nh, s), dtype=torch.float32, device="cuda")
+    dqkv = torch.zeros((b * s, 3 * hl), dtype=torch.bfloat16, device="cuda")
+    dot = torch.zeros((b, nh, s), dtype=torch.float32, device="cuda")
+    qd = dev(qkv)
+    dom.domino_attention_fwd(qd, 3 * hl, b, s, nh, d, ctx, lse)
+    dom.domino_attention_bwd_rope(qd, 3 * hl, ctx, dev(dctx), lse, dqkv, dot, b, s, nh, d, 10000.0)
+    torch.cuda.synchronize()
+    d4 = dctx.reshape(b, s, nh, d).transpose(0, 2, 1, 3).astype(np.float64)
+    rdq, rdk, rdv = O.attention_bwd(d4, q, k, v)
+    cos, sin = O.rope_tables(s, d, 10000.0)
+    rdq, rdk = O.rope_apply(rdq, cos, sin, inverse=True), O.rope_apply(rdk, cos, sin, inverse=True)
+    back = lambda m: m.transpose(0, 2, 1, 3).reshape(b * s, hl)
+    got = host(dqkv)
+    assert relerr(got[:, :hl], back(rdq)) < 1.5e-2
+    assert relerr(got[:, hl:2 * hl], back(rdk)) < 1.5e-2
+    assert relerr(got[:, 2 * hl:], back(rdv)) < 1.5e-2
+
+
 def test_colsum(dom):
     rng = np.random.default_rng(4)
     rows, n, ld = 1000, 264, 328

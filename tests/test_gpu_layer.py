@@ -169,6 +169,10 @@ MID = [
     synth.ShardConfig("mid-llama", 1024, 8, 4, 2, 1, 4, 2, 200, 5504, synth.ARCH_LLAMA, index=12),
     # head_dim 64 with a 256x256-tile sized problem
     synth.ShardConfig("mid-gpt-d64", 1024, 16, 2, 0, 2, 1, 4, 256, 4096, synth.ARCH_GPT, index=13),
+    # rotary embedding on heads of 80 columns (a separate pass over q and k in the forward) and of 64 columns (in the
+    # QKV product's epilogue, like the heads of 128 of mid-llama), sequences that end inside a tile
+    synth.ShardConfig("mid-llama-d80", 640, 8, 2, 1, 2, 2, 2, 136, 1792, synth.ARCH_LLAMA, index=15),
+    synth.ShardConfig("mid-llama-d64", 512, 8, 2, 0, 2, 1, 4, 72, 1536, synth.ARCH_LLAMA, index=16),
 ]
 
 
