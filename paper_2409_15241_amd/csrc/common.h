@@ -26,30 +26,33 @@ DEV float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
 DEV float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
 DEV float bf16_to_f32(bf16_t v) { return (float)v; }
 
-// tanh-form GeLU and its derivative (fp32); erf form selectable.
-DEV float fast_tanh(float x) {
-  // tanh(x) = 1 - 2/(exp(2x)+1); exp overflow gives the correct limit 1, underflow gives -1
-  float e = __expf(2.0f * x);
-  return 1.0f - 2.0f / (e + 1.0f);
-}
+// Logistic function on the hardware's 2^x and reciprocal units (1 ulp each; the results are rounded to bf16).
+// 2^x overflowing to +inf gives 1/inf = 0 and underflowing to 0 gives 1: the correct limits.
+DEV float sigmoid_f(float x) { return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x)); }
+
+// GeLU and its derivative (fp32); tanh form by default, erf form selectable.  With u = sqrt(2/pi) (x + 0.044715 x^3)
+// the tanh form 0.5 x (1 + tanh u) equals x * sigmoid(2 u), which costs one 2^x and one reciprocal; its derivative is
+// s + x s (1 - s) 2 u' with s = sigmoid(2 u).
 DEV float gelu_f(float x, bool tanh_form) {
   if (tanh_form) {
-    float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return 0.5f * x * (1.0f + fast_tanh(u));
+    const float x2 = x * x;
+    const float two_u = x * (1.5957691216057308f + 0.07135481627267621f * x2);     // 2 sqrt(2/pi) (1, 0.044715)
+    return x * sigmoid_f(two_u);
   }
   return 0.5f * x * (1.0f + erff(x * 0.7071067811865476f));
 }
 DEV float gelu_grad_f(float x, bool tanh_form) {
   if (tanh_form) {
-    float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    float t = fast_tanh(u);
-    return 0.5f * (1.0f + t) + 0.5f * x * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 0.134145f * x * x);
+    const float x2 = x * x;
+    const float two_u = x * (1.5957691216057308f + 0.07135481627267621f * x2);
+    const float s = sigmoid_f(two_u);
+    const float two_du = 1.5957691216057308f + 0.21406444881802863f * x2;          // d(2u)/dx
+    return s + x * s * (1.0f - s) * two_du;
   }
   float cdf = 0.5f * (1.0f + erff(x * 0.7071067811865476f));
   float pdf = __expf(-0.5f * x * x) * 0.3989422804014327f;
   return cdf + x * pdf;
 }
-DEV float sigmoid_f(float x) { return 1.0f / (1.0f + __expf(-x)); }
 
 // Rotary embedding (Sec. 5.4 names it for Llama-2): the pair (i, i + d/2) of a head at sequence position pos turns by
 // the angle pos * base^(-2 i / d).
