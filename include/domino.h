@@ -100,7 +100,9 @@ int domino_saved_slot(const domino_cfg* cfg, const char* name, size_t* offset, s
  *   attn_partial, mlp_partial: out [b,s,h]: what the two forward all-reduces would consume.
  *   y: out [b,s,h] or NULL.   saved: out, domino_saved_bytes().   workspace: scratch.
  *   streams[0..nstreams-1]: row slice i, with its q column pieces in index order, runs on
- *   streams[i % min(nstreams, p)]; streams beyond the first min(nstreams, p) are not used.
+ *   streams[i % m], m = min(nstreams, p); the forward uses no other stream.  (The backward, when m <= 2 and
+ *   nstreams >= 2 m and streams[0] is not being captured, puts slice i's weight gradients on streams[m + i % m],
+ *   beside the input gradients that follow them: few slices alone do not fill the chip.)
  *   Slices overlap only if their streams sit on distinct hardware queues: create
  *   the pool once, and let the process have more hardware queues than the pool has streams (HIP's
  *   GPU_MAX_HW_QUEUES, read when the runtime starts; domino_last_warning() tells when it looks too small).

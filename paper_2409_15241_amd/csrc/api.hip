@@ -175,13 +175,16 @@ bool capture_pool_ok(int nstreams, int p) {
   return ok(nstreams) && ok(nslice);
 }
 
-int begin_call(void* const* streams, int nstreams, int p) {
+thread_local bool g_capturing = false;     // streams[0] of the call being enqueued is under HIP graph capture
+
+int begin_call(void* const* streams, int nstreams, int p, bool backward = false) {
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
   g_pool = &g_pools[dev];
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
   HIP_TRY(hipStreamIsCapturing(static_cast<hipStream_t>(streams[0]), &cs), "hipStreamIsCapturing");
-  if (cs != hipStreamCaptureStatusNone) {
+  g_capturing = cs != hipStreamCaptureStatusNone;
+  if (g_capturing) {
     if (!capture_pool_ok(nstreams, p))
       return fail(DOMINO_ERR_UNSUPPORTED, "streams[0] is being captured into a HIP graph with a pool of %d streams for %d row "
                   "slices: capture is supported for pools of 1, 2 or 4 streams only (see domino_capture_supported)", nstreams, p);
@@ -190,7 +193,8 @@ int begin_call(void* const* streams, int nstreams, int p) {
   } else {
     g_pool->used = 0;
   }
-  note_hw_queues(p < nstreams ? p : nstreams);
+  const int nslice = p < nstreams ? p : nstreams;
+  note_hw_queues((backward && !g_capturing && nslice <= 2 && nstreams >= 2 * nslice) ? 2 * nslice : nslice);     // streams with launches in flight
   return DOMINO_OK;
 }
 
@@ -321,15 +325,27 @@ struct BwdLayer {
 // which stream of the pool carries which piece (Sec. 4.3.1: a fixed pool, picked by index)
 // Row slice i runs on streams[i % nslice] with all its column pieces: on one GPU there is no all-reduce for a
 // piece to overlap, and pieces on streams of their own were measured slower (the slices already fill the chip).
+// With one or two slices in flight and at least twice as many streams in the pool, the backward puts a slice's weight
+// gradients on a second stream of its own, streams[nslice + i % nslice]: the weight gradient of a product then runs
+// beside the input gradients that follow it on the slice's stream (Sec. 4.1.2 runs it beside the all-reduce of the
+// input gradient).  One or two launches have too few tiles for 256 compute units (11-12 % faster steps on the
+// shards configured with p = 2); from four launches in flight on the chip is full and more only slow each other
+// down (the 13B shard with 4 slices and 4 such extra streams: 630 instead of 790 TFLOP/s).
 struct StreamPlan {
   void* const* streams;
   int ns, p, nslice;
-  StreamPlan(void* const* s, int n, int p_) : streams(s), ns(n), p(p_), nslice(p_ < n ? p_ : n) {}
+  bool side;             // weight gradients on streams of their own
+  // (not under graph capture: instantiating a graph captured with the weight gradients on streams of their own has
+  // crashed inside the runtime, so a captured call keeps them on the slices' streams)
+  StreamPlan(void* const* s, int n, int p_)
+      : streams(s), ns(n), p(p_), nslice(p_ < n ? p_ : n), side(!g_capturing && (p_ < n ? p_ : n) <= 2 && n >= 2 * (p_ < n ? p_ : n)) {}
   hipStream_t slice(int i) const { return as_stream(streams[i % nslice]); }
-  // streams that a call touches: the first nslice
-  std::vector<char> used() const {
+  hipStream_t second(int i) const { return as_stream(streams[(side ? nslice : 0) + i % nslice]); }
+  int in_flight(bool backward) const { return (backward && side) ? 2 * nslice : nslice; }
+  // streams that a call touches: the first nslice, in the backward also the weight-gradient streams
+  std::vector<char> used(bool backward = false) const {
     std::vector<char> u(ns, 0);
-    for (int k = 0; k < nslice; ++k) u[k] = 1;
+    for (int k = 0; k < in_flight(backward); ++k) u[k] = 1;
     return u;
   }
 };
@@ -432,12 +448,10 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
   }
   // F4: (XA) * B_j, one piece per column slice, written in place into the full-width buffer
   for (int j = 0; j < L.q; ++j) {
-    {
-      ProfScope ps(PC_GEMM_OUT, st);
-      const size_t cj = (size_t)j * L.hq * 2;
-      GemmArgs a = gemm_args(ctx, L.hl, at(P->w_o, cj), L.h, at(B.attn_partial, rh + cj), L.h, Ms, L.hq, L.hl);
-      LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "out-projection piece");
-    }
+    ProfScope ps(PC_GEMM_OUT, st);
+    const size_t cj = (size_t)j * L.hq * 2;
+    GemmArgs a = gemm_args(ctx, L.hl, at(P->w_o, cj), L.h, at(B.attn_partial, rh + cj), L.h, Ms, L.hq, L.hl);
+    LAUNCH(gemm_launch(GEMM_NN, EPI_STORE, a, -1, st), "out-projection piece");
   }                                                       // column synchronisation before Norm2: stream order
   }
   if (!(parts & DOMINO_FWD_MLP)) return DOMINO_OK;
@@ -482,14 +496,14 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
 // Weight gradients are summed over the row slices in slice order: slice i's product into a matrix waits for
 // slice i-1's product into the same matrix (one event per matrix; the fifth is for the vector gradients).
 struct WgChain {
-  hipStream_t prev = nullptr;
+  hipStream_t prev = nullptr, prev_w = nullptr;      // the previous slice's stream and weight-gradient stream
   hipEvent_t done[5] = {}, cur[5] = {};
 };
 
 // Backward of row slice i of one block; within the slice each input gradient is enqueued before the weight
 // gradient of the same product (Sec. 4.1.2).
-int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStream_t st, const BwdLayer& B, int i,
-                      WgChain& wg, int parts = DOMINO_BWD_ALL) {
+int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStream_t st, hipStream_t wst, const BwdLayer& B,
+                      int i, WgChain& wg, int parts = DOMINO_BWD_ALL) {
   const domino_params* P = B.P;
   const domino_grads* G = B.G;
   const void* saved = B.saved;
@@ -520,18 +534,30 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   auto area = [&](int k) { return red + L.area_off[k]; };
   const int beta = (i > 0 || B.accumulate) ? 1 : 0;
   const bool chain = wg.prev && wg.prev != st;
+  const bool chain_w = wg.prev_w && wg.prev_w != wst;
+  const bool side = wst != st;
 
-  auto wgrad = [&](int which, int cls, const void* A, long lda, const void* Bm, long ldb, float* C, long ldc,
+  // the point on the slice's stream after which an operand of a weight gradient exists (only needed when the weight
+  // gradients run on a stream of their own)
+  auto produced = [&](hipEvent_t* ev) -> int {
+    *ev = nullptr;
+    if (!side) return DOMINO_OK;
+    TRY(next_sync_event(ev));
+    HIP_TRY(hipEventRecord(*ev, st), "hipEventRecord");
+    return DOMINO_OK;
+  };
+  auto wgrad = [&](int which, int cls, hipEvent_t dep, const void* A, long lda, const void* Bm, long ldb, float* C, long ldc,
                    int M, int N) -> int {
-    if (chain) HIP_TRY(hipStreamWaitEvent(st, wg.done[which], 0), "hipStreamWaitEvent");
+    if (dep) HIP_TRY(hipStreamWaitEvent(wst, dep, 0), "hipStreamWaitEvent");
+    if (chain_w) HIP_TRY(hipStreamWaitEvent(wst, wg.done[which], 0), "hipStreamWaitEvent");
     {
-      ProfScope ps(cls, st);
+      ProfScope ps(cls, wst);
       GemmArgs a = gemm_args(A, lda, Bm, ldb, C, ldc, M, N, Ms);
       a.beta = beta;
-      LAUNCH(gemm_launch(GEMM_TN, EPI_ACC_F32, a, -1, st), "weight gradient");
+      LAUNCH(gemm_launch(GEMM_TN, EPI_ACC_F32, a, -1, wst), "weight gradient");
     }
     TRY(next_sync_event(&wg.cur[which]));
-    HIP_TRY(hipEventRecord(wg.cur[which], st), "hipEventRecord");
+    HIP_TRY(hipEventRecord(wg.cur[which], wst), "hipEventRecord");
     return DOMINO_OK;
   };
   auto colsum = [&](const void* g, long ld, int n, int k) -> int {
@@ -551,6 +577,8 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   };
 
   if (parts & DOMINO_BWD_MLP) {
+  hipEvent_t have_dy;          // in a stack dy is what the block above has just written on this stream
+  TRY(produced(&have_dy));
   {  // B1 + B3: input gradient of the down-projection (all q column slices inside the K loop), activation backward fused
     ProfScope ps(PC_DGRAD_DOWN, st);
     GemmArgs a = gemm_args(dyi, L.h, P->w_down, L.h, d_pre, L.upc, Ms, L.fl, L.h);
@@ -558,25 +586,29 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     if (L.llama) { a.n_split = L.fl; LAUNCH(gemm_launch(GEMM_NT, EPI_DSWIGLU, a, -1, st), "mlp-down input gradient"); }
     else LAUNCH(gemm_launch(GEMM_NT, EPI_DGELU, a, -1, st), "mlp-down input gradient");
   }
-  TRY(wgrad(0, PC_WGRAD_DOWN, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
+  TRY(wgrad(0, PC_WGRAD_DOWN, have_dy, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
+  hipEvent_t have_dpre;
+  TRY(produced(&have_dpre));
   {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
     ProfScope ps(PC_DGRAD_UP, st);
     GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(B.dln2_partial, rh), L.h, Ms, L.h, L.upc);
     LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "mlp-up input gradient");
   }
-  TRY(wgrad(1, PC_WGRAD_UP, ln2, L.h, d_pre, L.upc, G->w_up, L.upc, L.h, L.upc));
+  TRY(wgrad(1, PC_WGRAD_UP, have_dpre, ln2, L.h, d_pre, L.upc, G->w_up, L.upc, L.h, L.upc));
   if (!L.llama) TRY(colsum(d_pre, L.upc, L.fl, AREA_BUP));
   }
   if (parts & DOMINO_BWD_ATTN) {
   // B5
   TRY(norm_bwd(at(B.dln2_partial, rh), B.dln2_others ? at(B.dln2_others, rh) : nullptr, x1, P->norm2_g, mean2, rstd2,
                dyi, dx1, AREA_G2, AREA_B2, L.llama ? -1 : AREA_BDOWN, L.llama ? -1 : AREA_BO));
+  hipEvent_t have_dx1;
+  TRY(produced(&have_dx1));
   {  // B6
     ProfScope ps(PC_DGRAD_OUT, st);
     GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
     LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "out-projection input gradient");
   }
-  TRY(wgrad(2, PC_WGRAD_OUT, ctx, L.hl, dx1, L.h, G->w_o, L.h, L.hl, L.h));
+  TRY(wgrad(2, PC_WGRAD_OUT, have_dx1, ctx, L.hl, dx1, L.h, G->w_o, L.h, L.hl, L.h));
   {  // B7
     ProfScope ps(PC_ATTN_BWD, st);
     AttnArgs a{};
@@ -586,12 +618,14 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     a.rope = L.llama ? 1 : 0; a.rope_log2_base = log2f(cfg->rope_base);   // dq, dk are turned back where they are stored
     LAUNCH(attention_bwd_launch(a, st), "attention backward");
   }
+  hipEvent_t have_dqkv;
+  TRY(produced(&have_dqkv));
   {  // B8: input gradient of QKV: the tensor the fourth all-reduce would sum
     ProfScope ps(PC_DGRAD_QKV, st);
     GemmArgs a = gemm_args(dqkv, 3 * L.hl, P->w_qkv, 3 * L.hl, at(B.dln1_partial, rh), L.h, Ms, L.h, 3 * L.hl);
     LAUNCH(gemm_launch(GEMM_NT, EPI_STORE, a, -1, st), "qkv input gradient");
   }
-  TRY(wgrad(3, PC_WGRAD_QKV, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
+  TRY(wgrad(3, PC_WGRAD_QKV, have_dqkv, ln1, L.h, dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl));
   if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, AREA_BQKV));
   }
   if (parts & DOMINO_BWD_NORM1) {
@@ -619,7 +653,11 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     HIP_TRY(hipEventRecord(wg.cur[4], st), "hipEventRecord");
   }
 
+  // the slice's stream ends after the slice's weight gradients: whatever follows on it (the same slice of the block
+  // below in a stack, a later part, the join) may overwrite what they read
+  if (side) TRY(edge(wst, st));
   wg.prev = st;
+  wg.prev_w = wst;
   for (int k = 0; k < 5; ++k) wg.done[k] = wg.cur[k];
   return DOMINO_OK;
 }
@@ -740,15 +778,15 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   if (workspace_bytes < L.ws_total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, L.ws_total);
   std::lock_guard<std::mutex> lock(g_mutex);
-  TRY(begin_call(streams, nstreams, L.p));
-  ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
+  TRY(begin_call(streams, nstreams, L.p, true));
+  ConcurrencyScope conc(StreamPlan(streams, nstreams, L.p).in_flight(true));
 
   B.red = reinterpret_cast<float*>(at(workspace, L.red));
   const StreamPlan S(streams, nstreams, L.p);
-  const std::vector<char> used = S.used();
+  const std::vector<char> used = S.used(true);
   TRY(fork_streams(S, used));
   WgChain wg;
-  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), B, i, wg, parts));
+  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), S.second(i), B, i, wg, parts));
   TRY(join_streams(S, used));
   return DOMINO_OK;
 }
@@ -818,15 +856,15 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   }
   TRY(check_streams(streams, nstreams));
   std::lock_guard<std::mutex> lock(g_mutex);
-  TRY(begin_call(streams, nstreams, L.p));
-  ConcurrencyScope conc(nstreams < L.p ? nstreams : L.p);
+  TRY(begin_call(streams, nstreams, L.p, true));
+  ConcurrencyScope conc(StreamPlan(streams, nstreams, L.p).in_flight(true));
 
   const StreamPlan S(streams, nstreams, L.p);
-  const std::vector<char> used = S.used();
+  const std::vector<char> used = S.used(true);
   TRY(fork_streams(S, used));
   for (int l = nlayers - 1; l >= 0; --l) {
     WgChain wg;
-    for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), layers[l], i, wg));
+    for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), S.second(i), layers[l], i, wg));
   }
   TRY(join_streams(S, used));
   return DOMINO_OK;

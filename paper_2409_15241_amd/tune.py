@@ -73,8 +73,9 @@ def tune(sc, pairs: Optional[List[Tuple[int, int]]] = None, streams: Iterable[in
     data = make_data(sc)
     for (p, q) in (pairs if pairs is not None else candidates(sc)):
         for ns in streams:
-            if ns > max(p, 1) and ns > 1:
-                continue          # more streams than row slices adds nothing (column pieces stay on their slice's stream)
+            if ns > 1 and ns > (2 * p if p <= 2 else p):
+                continue          # streams the library would not use: one per row slice, and with one or two slices
+                                  # a second one per slice for the backward's weight gradients
             ms = measure(sc.replace(p=p, q=q), ns, steps, warmup, data)
             table.append((p, q, ns, ms))
             if report:

@@ -346,17 +346,20 @@ def test_two_host_threads_with_their_own_pools(H):
                 np.testing.assert_array_equal(g.cpu().numpy(), ref["grads"][k], err_msg=k)
 
 
-def test_graph_replay_is_bitwise_the_eager_step(H):
+@pytest.mark.parametrize("p,nstreams", [(4, 4), (2, 4), (1, 2), (2, 2), (4, 1)],
+                         ids=["4slices-4streams", "2slices-4streams", "1slice-2streams", "2slices-2streams", "4slices-1stream"])
+def test_graph_replay_is_bitwise_the_eager_step(H, p, nstreams):
     """The step captured once in a HIP graph on streams[0] (the library forks and joins the pool inside the capture,
     allocates nothing and records no memset) and replayed several times, with eager steps and synchronisations in
-    between: every replay leaves the bits of the eager step."""
-    sc = TINY.replace(batch=4, p=4, q=2)
+    between: every replay leaves the bits of the eager step.  (With twice as many streams as slices an eager backward
+    runs the weight gradients on streams of their own; a captured one keeps them on the slices' streams.)"""
+    sc = TINY.replace(batch=4, p=p, q=2)
     params = synth.make_rank_params(sc, random_affine=True)
     x, dy = synth.make_activations(sc)
     others = synth.make_others(sc)
-    ref = run_gpu(H, sc, params, x, dy, others, nstreams=4)
-    buf = H.LayerBuffers(sc, params, x, dy, others, nstreams=4)
-    other = H.LayerBuffers(sc, params, x, dy, others, nstreams=4)       # eager work between the replays
+    ref = run_gpu(H, sc, params, x, dy, others, nstreams=1)
+    buf = H.LayerBuffers(sc, params, x, dy, others, nstreams=nstreams)
+    other = H.LayerBuffers(sc, params, x, dy, others, nstreams=nstreams)       # eager work between the replays
 
     def step():
         buf.forward()
