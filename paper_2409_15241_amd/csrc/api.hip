@@ -576,6 +576,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     return DOMINO_OK;
   };
 
+  hipEvent_t read_dy = nullptr;   // set once the down-projection's weight gradient, a reader of dy on the second stream, is enqueued
   if (parts & DOMINO_BWD_MLP) {
   hipEvent_t have_dy;          // in a stack dy is what the block above has just written on this stream
   TRY(produced(&have_dy));
@@ -587,6 +588,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     else LAUNCH(gemm_launch(GEMM_NT, EPI_DGELU, a, -1, st), "mlp-down input gradient");
   }
   TRY(wgrad(0, PC_WGRAD_DOWN, have_dy, act, L.fl, dyi, L.h, G->w_down, L.h, L.fl, L.h));        // B2
+  if (side) read_dy = wg.cur[0];
   hipEvent_t have_dpre;
   TRY(produced(&have_dpre));
   {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
@@ -629,6 +631,9 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   if (!L.llama) TRY(colsum(dqkv, 3 * L.hl, 3 * L.hl, AREA_BQKV));
   }
   if (parts & DOMINO_BWD_NORM1) {
+    // dx may be the tensor dy came in (a stack hands one tensor from block to block): its rows are overwritten only
+    // after the second stream's reader of dy is through (long since, in practice: it was the first thing enqueued there)
+    if (read_dy) HIP_TRY(hipStreamWaitEvent(st, read_dy, 0), "hipStreamWaitEvent");
     TRY(norm_bwd(at(B.dln1_partial, rh), B.dln1_others ? at(B.dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
                  dx1, at(B.dx, rh), AREA_G1, AREA_B1));
     // Vector gradients (norm gains and shifts, biases): the partial rows of all three parts of this slice lie in

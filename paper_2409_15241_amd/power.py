@@ -14,7 +14,9 @@ import os
 import threading
 import time
 
-if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:   # one hardware queue per pool stream (see bench.py)
+# one hardware queue per pool stream (see bench.py); only when this is the program: a process that imports the module
+# may have started the HIP runtime already, which reads the variable once
+if __name__ == "__main__" and int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
     os.environ["GPU_MAX_HW_QUEUES"] = "8"
 
 

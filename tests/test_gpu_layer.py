@@ -450,19 +450,17 @@ def test_graph_replay_with_other_pools(H, nstreams):
     buf.sync()
 
 
-def test_hardware_queue_note(H):
+def test_hardware_queue_note(H, hw_queues_at_start):
     """Four slices on four streams with fewer hardware queues than streams + 1 configured: the library says so
     once; with enough queues it stays silent."""
-    import os
     from paper_2409_15241_amd import domino as D
     sc = TINY.replace(batch=4, p=4, q=2)
     params = synth.make_rank_params(sc, random_affine=True)
     x, dy = synth.make_activations(sc)
     buf = H.LayerBuffers(sc, params, x, dy, synth.make_others(sc), nstreams=4)
     buf.forward(); buf.sync()
-    have = int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0)
     note = D.domino_last_warning()
-    if have >= 5:
+    if hw_queues_at_start >= 5:
         assert note == ""
     else:
         assert "GPU_MAX_HW_QUEUES" in note and ">= 5" in note
