@@ -29,15 +29,22 @@ DEFAULT_WORKLOAD = "gpt3-13b"      # the shard the throughput target is quoted o
 
 def gemm_flops_per_launch(sc):
     """Algorithmic flops of one launch of each GEMM step class (one row slice; one column piece for
-    the two row-parallel products)."""
+    the two row-parallel products; the weight gradients contract over one slice's rows for p <= 2 and over all rows
+    of the block, in one launch per matrix, beyond that)."""
     Ms = sc.tokens // sc.p
+    Mw = wgrad_rows(sc)
     h, hl, fl, upc, hq = sc.hidden, sc.h_local, sc.f_local, sc.up_cols, sc.hidden // sc.q
     return {
         "gemm_qkv": 2.0 * Ms * h * 3 * hl, "gemm_out": 2.0 * Ms * hl * hq, "gemm_up": 2.0 * Ms * h * upc,
-        "gemm_down": 2.0 * Ms * fl * hq, "dgrad_down": 2.0 * Ms * h * fl, "wgrad_down": 2.0 * Ms * fl * h,
-        "dgrad_up": 2.0 * Ms * upc * h, "wgrad_up": 2.0 * Ms * h * upc, "dgrad_out": 2.0 * Ms * h * hl,
-        "wgrad_out": 2.0 * Ms * hl * h, "dgrad_qkv": 2.0 * Ms * 3 * hl * h, "wgrad_qkv": 2.0 * Ms * h * 3 * hl,
+        "gemm_down": 2.0 * Ms * fl * hq, "dgrad_down": 2.0 * Ms * h * fl, "wgrad_down": 2.0 * Mw * fl * h,
+        "dgrad_up": 2.0 * Ms * upc * h, "wgrad_up": 2.0 * Mw * h * upc, "dgrad_out": 2.0 * Ms * h * hl,
+        "wgrad_out": 2.0 * Mw * hl * h, "dgrad_qkv": 2.0 * Ms * 3 * hl * h, "wgrad_qkv": 2.0 * Mw * h * 3 * hl,
     }
+
+
+def wgrad_rows(sc):
+    """Rows one weight-gradient launch contracts over (the library's rule: merged over the slices when p > 2)."""
+    return sc.tokens if sc.p > 2 else sc.tokens // sc.p
 
 
 def algorithmic_flops(sc):
@@ -340,7 +347,7 @@ def main():
 
     if roofline is not None and roofline["kernel"].startswith("gemm_kernel<TN"):
         # context for `achieved`: the same launches with the chip to themselves (one stream, nothing else running)
-        Ms = sc.tokens // sc.p
+        Ms = wgrad_rows(sc)
         shapes = [(sc.f_local, sc.hidden), (sc.hidden, sc.up_cols), (sc.h_local, sc.hidden), (sc.hidden, 3 * sc.h_local)]
         tile = 2 if min(args.streams, sc.p) >= 3 else -1       # the tile the layer call picks
         tot_ms, tot_fl = 0.0, 0.0
@@ -350,7 +357,7 @@ def main():
             Cw = torch.zeros(Mw, Nw, device="cuda", dtype=torch.float32)
             torch.cuda.synchronize()
             run = lambda: domino.domino_gemm(domino.GEMM_TN, domino.EPI_ACC_F32, tile, A, Mw, B, Nw, Cw, Nw, Mw, Nw, Ms,
-                                             beta=1, stream=s0)
+                                             beta=0 if sc.p > 2 else 1, stream=s0)
             run()
             tot_ms += timed(run, 10)
             tot_fl += 2.0 * Ms * Mw * Nw

@@ -118,8 +118,12 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* params,
  * formed before its weight gradient).  x and saved are those of the forward call.
  *   dln2_others, dln1_others: [b,s,h] or NULL: the other ranks' sums of the two backward all-reduces.
  *   dln2_partial, dln1_partial: out [b,s,h]: this rank's input gradients of MLP-up and QKV.
- *   dx: out [b,s,h].   grads: fp32; accumulate != 0 adds to their contents, else overwrites.
- * Weight gradients are summed over the row slices in slice order (run-to-run identical). */
+ *   dx: out [b,s,h]; must not overlap dy.   grads: fp32; accumulate != 0 adds to their contents, else overwrites.
+ * Weight gradients: with p <= 2 each slice adds its share right behind its input gradient, in slice order; with
+ * p > 2 one launch per matrix contracts over all rows of the block after the last slice's input gradients (every
+ * further slice would otherwise read and rewrite the whole fp32 gradient; on one GPU that traffic is time), the four
+ * launches spread over the slices' streams.  Either way the order of the sums is fixed: results are run-to-run
+ * identical and do not depend on the stream pool. */
 int domino_layer_bwd(const domino_cfg* cfg, const domino_params* params, const void* saved,
                      const void* x, const void* dy,
                      const void* dln2_others, const void* dln1_others,
@@ -178,7 +182,8 @@ typedef struct domino_stack_bwd_io {
 } domino_stack_bwd_io;
 
 /* Workspace bytes of a stack of nlayers blocks (1..1024): one block's workspace, one area of partial
- * vector-gradient sums per further block, and the [b,s,h] gradient handed from block to block.  0 on error. */
+ * vector-gradient sums per further block, two [b,s,h] gradients handed from block to block in turn and, for
+ * p > 2, a second set of the activation gradients that the weight gradients read.  0 on error. */
 size_t domino_stack_workspace_bytes(const domino_cfg* cfg, int nlayers);
 
 /* Forward of nlayers blocks of the same configuration, params[l] and io[l] being block l's (host arrays of
@@ -193,9 +198,11 @@ int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
 
 /* Backward of the stack for L = sum(y_last * dy): blocks nlayers-1 .. 0, dx of one being dy of the one below
  * (kept in the workspace).  grads[l] are block l's gradients (host array of nlayers structs); accumulate as
- * in domino_layer_bwd.  Within a block the weight and vector gradients are still summed in slice order (slice
- * i's sum into a gradient waits for slice i-1's); between blocks a slice goes on without waiting for the
- * others.  Results are bitwise those of nlayers calls of domino_layer_bwd. */
+ * in domino_layer_bwd.  Within a block the weight and vector gradients are summed as domino_layer_bwd sums them.
+ * For p <= 2 a slice goes on from block to block without waiting for the others; for p > 2 the slices of a block
+ * meet before its weight gradients (one launch per matrix over all rows), after which each stream goes on with
+ * its slice of the block below while the other streams' launches still run (the tensors those read are kept
+ * twice and used in turn).  Results are bitwise those of nlayers calls of domino_layer_bwd. */
 int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* dy,
                      const domino_stack_bwd_io* io, void* dx, const domino_grads* grads, int accumulate,
                      void* workspace, size_t workspace_bytes, void* const* streams, int nstreams);

@@ -386,6 +386,11 @@ int check_bwd_layer(const Layout& L, const BwdLayer& B, int parts = DOMINO_BWD_A
     return fail(DOMINO_ERR_NULL_POINTER, "a weight or norm-gain gradient pointer is NULL");
   if (!L.llama && (!G->norm1_b || !G->norm2_b || !G->b_qkv || !G->b_o || !G->b_up || !G->b_down))
     return fail(DOMINO_ERR_NULL_POINTER, "a GPT bias or norm-shift gradient pointer is NULL");
+  if ((parts & DOMINO_BWD_MLP) && (parts & DOMINO_BWD_NORM1)) {      // the down-projection's weight gradient may read dy after dx is written
+    const size_t bytes = (size_t)L.M * L.h * 2;
+    const char *a = static_cast<const char*>(B.dy), *b = static_cast<const char*>(B.dx);
+    if (a < b + bytes && b < a + bytes) return fail(DOMINO_ERR_INVALID_ARG, "dx overlaps dy");
+  }
   return DOMINO_OK;
 }
 
@@ -502,8 +507,20 @@ struct WgChain {
 
 // Backward of row slice i of one block; within the slice each input gradient is enqueued before the weight
 // gradient of the same product (Sec. 4.1.2).
-int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStream_t st, hipStream_t wst, const BwdLayer& B,
-                      int i, WgChain& wg, int parts = DOMINO_BWD_ALL) {
+// The gradients of a block's intermediate activations that its weight gradients read (whole tensors, all row slices).
+struct GradBufs { char *d_pre, *dx1, *dqkv; };
+GradBufs grad_bufs(const Layout& L, void* ws) { return {at(ws, L.d_pre), at(ws, L.dx1), at(ws, L.dqkv)}; }
+
+// With more than two row slices the weight gradients are not formed slice by slice: one launch per matrix contracts
+// over all rows of the block after the last slice's input gradients (enqueue_merged_wgrads).  Slice by slice, every
+// slice after the first reads and rewrites the whole fp32 gradient (for the 13B shard 0.94 GB of 9.4 GB per step at
+// p = 4) in launches a quarter as deep; the step sits on the board's power cap, so the saved traffic is saved time
+// (3.5-4.5 % of the step).  With one or two slices the slice-by-slice launches on second streams are faster (they fill
+// a chip that two slices leave half empty), so the rule follows p alone and the arithmetic does not depend on the pool.
+inline bool merged_wgrads(const Layout& L) { return L.p > 2; }
+
+int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const GradBufs& gb, hipStream_t st, hipStream_t wst,
+                      const BwdLayer& B, int i, WgChain& wg, int parts = DOMINO_BWD_ALL, hipEvent_t before_dx = nullptr) {
   const domino_params* P = B.P;
   const domino_grads* G = B.G;
   const void* saved = B.saved;
@@ -525,10 +542,10 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   const float* rstd1 = reinterpret_cast<const float*>(at(saved, L.rstd1)) + r0;
   const float* mean2 = reinterpret_cast<const float*>(at(saved, L.mean2)) + r0;
   const float* rstd2 = reinterpret_cast<const float*>(at(saved, L.rstd2)) + r0;
-  char* d_pre = at(ws, L.d_pre + r0 * L.upc * 2);
-  char* dx1 = at(ws, L.dx1 + rh);
+  char* d_pre = gb.d_pre + r0 * L.upc * 2;
+  char* dx1 = gb.dx1 + rh;
   char* dctx = at(ws, L.dctx + r0 * L.hl * 2);
-  char* dqkv = at(ws, L.dqkv + r0 * 3 * L.hl * 2);
+  char* dqkv = gb.dqkv + r0 * 3 * L.hl * 2;
   float* dot = reinterpret_cast<float*>(at(ws, L.dot)) + (size_t)i * (L.b / L.p) * L.nl * L.s;
   float* red = B.red + (size_t)i * L.red_floats;
   auto area = [&](int k) { return red + L.area_off[k]; };
@@ -536,6 +553,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   const bool chain = wg.prev && wg.prev != st;
   const bool chain_w = wg.prev_w && wg.prev_w != wst;
   const bool side = wst != st;
+  const bool merged = merged_wgrads(L);
 
   // the point on the slice's stream after which an operand of a weight gradient exists (only needed when the weight
   // gradients run on a stream of their own)
@@ -548,6 +566,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   };
   auto wgrad = [&](int which, int cls, hipEvent_t dep, const void* A, long lda, const void* Bm, long ldb, float* C, long ldc,
                    int M, int N) -> int {
+    if (merged) return DOMINO_OK;      // formed over all slices at once, after the last slice
     if (dep) HIP_TRY(hipStreamWaitEvent(wst, dep, 0), "hipStreamWaitEvent");
     if (chain_w) HIP_TRY(hipStreamWaitEvent(wst, wg.done[which], 0), "hipStreamWaitEvent");
     {
@@ -634,6 +653,9 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
     // dx may be the tensor dy came in (a stack hands one tensor from block to block): its rows are overwritten only
     // after the second stream's reader of dy is through (long since, in practice: it was the first thing enqueued there)
     if (read_dy) HIP_TRY(hipStreamWaitEvent(st, read_dy, 0), "hipStreamWaitEvent");
+    // in a stack with merged weight gradients dx goes into the tensor that the block above took its dy from, and that
+    // block's down-projection weight gradient (on another stream, enqueued a whole block ago) reads all of it
+    if (before_dx) HIP_TRY(hipStreamWaitEvent(st, before_dx, 0), "hipStreamWaitEvent");
     TRY(norm_bwd(at(B.dln1_partial, rh), B.dln1_others ? at(B.dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
                  dx1, at(B.dx, rh), AREA_G1, AREA_B1));
     // Vector gradients (norm gains and shifts, biases): the partial rows of all three parts of this slice lie in
@@ -667,17 +689,71 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, hipStrea
   return DOMINO_OK;
 }
 
-// workspace of a stack: one block's workspace, the partial-sum areas of the other blocks, and the gradient
-// tensor handed from block to block
+// The weight gradients of the matrices that `parts` owns, each in one launch over all rows of the block (see
+// merged_wgrads): enqueued after the slices of the block, the launches spread over the slices' streams starting at
+// streams[turn % nslice] (largest first; a stack turns the assignment from block to block so that no stream always
+// gets the big ones), after every stream's slices have got that far.  The sum over the rows runs inside the
+// kernel in a fixed order, so results are run-to-run identical.  done / done_on (4 entries, by matrix: down, up, qkv,
+// out; or NULL): an event recorded after each launch and the stream it ran on.
+int enqueue_merged_wgrads(const Layout& L, const StreamPlan& S, const GradBufs& gb, const BwdLayer& B, int parts, int turn,
+                          hipEvent_t* done = nullptr, hipStream_t* done_on = nullptr) {
+  const char* sv = static_cast<const char*>(B.saved);
+  const domino_grads* G = B.G;
+  struct { int part, cls; const void* A; long lda; const void* Bm; long ldb; float* C; long ldc; int M, N; } w[4] = {
+    {DOMINO_BWD_MLP, PC_WGRAD_DOWN, sv + L.act, L.fl, B.dy, L.h, G->w_down, L.h, L.fl, L.h},
+    {DOMINO_BWD_MLP, PC_WGRAD_UP, sv + L.ln2, L.h, gb.d_pre, L.upc, G->w_up, L.upc, L.h, L.upc},
+    {DOMINO_BWD_ATTN, PC_WGRAD_QKV, sv + L.ln1, L.h, gb.dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl},
+    {DOMINO_BWD_ATTN, PC_WGRAD_OUT, sv + L.ctx, L.hl, gb.dx1, L.h, G->w_o, L.h, L.hl, L.h}};
+  if (!(parts & (DOMINO_BWD_MLP | DOMINO_BWD_ATTN))) return DOMINO_OK;
+  // every stream's slices must have got this far: the streams meet on streams[0] and part again, the same join and
+  // fork that end one call and begin the next (direct waits of every stream for every other one say the same with
+  // more edges, but a HIP graph captured with them crashed the runtime when it was instantiated)
+  if (S.nslice > 1) {
+    const std::vector<char> slices = S.used(false);
+    TRY(join_streams(S, slices));
+    TRY(fork_streams(S, slices));
+  }
+  int slot = 0;
+  for (int m = 0; m < 4; ++m) {
+    if (!(parts & w[m].part)) continue;
+    hipStream_t st = S.slice((slot++ + turn) % S.nslice);
+    {
+      ProfScope ps(w[m].cls, st);
+      GemmArgs a = gemm_args(w[m].A, w[m].lda, w[m].Bm, w[m].ldb, w[m].C, w[m].ldc, w[m].M, w[m].N, L.M);
+      a.beta = B.accumulate ? 1 : 0;
+      LAUNCH(gemm_launch(GEMM_TN, EPI_ACC_F32, a, -1, st), "weight gradient");
+    }
+    if (done) {
+      TRY(next_sync_event(&done[m]));
+      HIP_TRY(hipEventRecord(done[m], st), "hipEventRecord");
+      done_on[m] = st;
+    }
+  }
+  return DOMINO_OK;
+}
+
+// workspace of a stack: one block's workspace, the partial-sum areas of the other blocks, two gradient tensors
+// handed from block to block in turn (a block reads its dy from one and writes its dx into the other) and, when the
+// weight gradients are merged, a second set of the tensors they read, so that the block below can run on while
+// they are formed
 struct StackLayout {
-  size_t red_bytes, extra_red, dmid, total;
+  size_t red_bytes, extra_red, dmid[2], d_pre2, dx1_2, dqkv2, total;
 };
 StackLayout stack_layout(const Layout& L, int nlayers) {
   StackLayout s{};
+  const size_t Mz = (size_t)L.M;
   s.red_bytes = align_up((size_t)L.p * L.red_floats * 4);
   s.extra_red = L.ws_total;
-  s.dmid = s.extra_red + (size_t)(nlayers - 1) * s.red_bytes;
-  s.total = s.dmid + align_up((size_t)L.M * L.h * 2);
+  size_t o = s.extra_red + (size_t)(nlayers - 1) * s.red_bytes;
+  auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
+  s.dmid[0] = take(Mz * L.h * 2);
+  s.dmid[1] = take(Mz * L.h * 2);
+  if (merged_wgrads(L) && nlayers > 1) {
+    s.d_pre2 = take(Mz * L.upc * 2);
+    s.dx1_2 = take(Mz * L.h * 2);
+    s.dqkv2 = take(Mz * 3 * L.hl * 2);
+  }
+  s.total = o;
   return s;
 }
 constexpr int MAX_STACK_LAYERS = 1024;
@@ -791,7 +867,9 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   const std::vector<char> used = S.used(true);
   TRY(fork_streams(S, used));
   WgChain wg;
-  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), S.second(i), B, i, wg, parts));
+  const GradBufs gb = grad_bufs(L, workspace);
+  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, gb, S.slice(i), S.second(i), B, i, wg, parts));
+  if (merged_wgrads(L)) TRY(enqueue_merged_wgrads(L, S, gb, B, parts, 0));
   TRY(join_streams(S, used));
   return DOMINO_OK;
 }
@@ -848,15 +926,15 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   if (!workspace) return fail(DOMINO_ERR_NULL_POINTER, "workspace is NULL");
   const StackLayout SL = stack_layout(L, nlayers);
   if (workspace_bytes < SL.total) return fail(DOMINO_ERR_WORKSPACE_TOO_SMALL, "workspace holds %zu bytes, %zu needed", workspace_bytes, SL.total);
-  void* dmid = at(workspace, SL.dmid);
   std::vector<BwdLayer> layers(nlayers);
   for (int l = 0; l < nlayers; ++l) {
     float* red = reinterpret_cast<float*>(l == 0 ? at(workspace, L.red) : at(workspace, SL.extra_red + (size_t)(l - 1) * SL.red_bytes));
-    // the gradient handed down the stack lives in one tensor: a slice's last kernel of block l writes the rows
-    // that the same slice of block l-1, next on the same stream, reads
-    layers[l] = BwdLayer{&params[l], &grads[l], io[l].saved, io[l].x, l == nlayers - 1 ? dy : dmid,
+    // the gradient handed down the stack lives in two tensors taken in turn: a slice's last kernel of block l writes
+    // the rows that the same slice of block l-1, next on the same stream, reads
+    const int turn = (nlayers - 1 - l) & 1;
+    layers[l] = BwdLayer{&params[l], &grads[l], io[l].saved, io[l].x, l == nlayers - 1 ? dy : at(workspace, SL.dmid[turn ^ 1]),
                          io[l].dln2_others, io[l].dln1_others, io[l].dln2_partial, io[l].dln1_partial,
-                         l == 0 ? dx : dmid, red, accumulate};
+                         l == 0 ? dx : at(workspace, SL.dmid[turn]), red, accumulate};
     TRY(check_bwd_layer(L, layers[l]));
   }
   TRY(check_streams(streams, nstreams));
@@ -867,9 +945,27 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   const StreamPlan S(streams, nstreams, L.p);
   const std::vector<char> used = S.used(true);
   TRY(fork_streams(S, used));
+  const bool merged = merged_wgrads(L);
+  GradBufs gb[2] = {grad_bufs(L, workspace), grad_bufs(L, workspace)};
+  if (merged && nlayers > 1) gb[1] = GradBufs{at(workspace, SL.d_pre2), at(workspace, SL.dx1_2), at(workspace, SL.dqkv2)};
+  // merged weight gradients of the last block that used each set of gradient tensors: by matrix (down, up, qkv, out)
+  hipEvent_t wdone[2][4] = {};
+  hipStream_t won[2][4] = {};
   for (int l = nlayers - 1; l >= 0; --l) {
+    const int turn = (nlayers - 1 - l) & 1;
+    if (merged) {
+      // this block overwrites the set of tensors that the merged weight gradients of the block two above read: they
+      // were enqueued a whole block ago, so these waits order without stalling
+      for (int k = 0; k < S.nslice; ++k)
+        for (int m = 1; m < 4; ++m)
+          if (wdone[turn][m] && won[turn][m] != S.slice(k)) HIP_TRY(hipStreamWaitEvent(S.slice(k), wdone[turn][m], 0), "hipStreamWaitEvent");
+    }
     WgChain wg;
-    for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, S.slice(i), S.second(i), layers[l], i, wg));
+    // dx of this block goes where the block above read its dy: its down-projection weight gradient must be through
+    hipEvent_t before_dx = merged ? wdone[turn ^ 1][0] : nullptr;
+    for (int i = 0; i < L.p; ++i)
+      TRY(enqueue_bwd_slice(L, cfg, workspace, gb[turn], S.slice(i), S.second(i), layers[l], i, wg, DOMINO_BWD_ALL, before_dx));
+    if (merged) TRY(enqueue_merged_wgrads(L, S, gb[turn], layers[l], DOMINO_BWD_ALL, nlayers - 1 - l, wdone[turn], won[turn]));
   }
   TRY(join_streams(S, used));
   return DOMINO_OK;

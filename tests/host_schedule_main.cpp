@@ -43,6 +43,7 @@ struct Op {
   bool vec_reduce = false;           // LAUNCH of the vector-gradient reduction
 };
 static std::vector<Op> g_ops;
+static long g_rows = 0;              // rows (batch x sequence) of the configuration under test
 static bool g_capturing = false;
 static int g_failures = 0;
 static std::string g_case;
@@ -273,6 +274,11 @@ static void check_call(int first, hipStream_t s0, int p, bool capturing) {
         if (r.write) { per_vector[r.base].push_back(i); break; }
   }
   for (auto& kv : per_matrix) {
+    // slice by slice for one or two slices, one launch over all rows beyond that; either way every row exactly once
+    EXPECT((int)kv.second.size() == (p > 2 ? 1 : p), "%zu weight-gradient launches into one matrix for %d slices", kv.second.size(), p);
+    long rows = 0;
+    for (int i : kv.second) rows += g_ops[i].regions[0].rows;
+    EXPECT(rows == g_rows, "the weight-gradient launches into one matrix contract over %ld rows of %ld", rows, g_rows);
     for (size_t k = 1; k < kv.second.size(); ++k)
       EXPECT(A.hb(kv.second[k - 1], kv.second[k]), "weight gradients %d and %d into one matrix are not ordered", kv.second[k - 1], kv.second[k]);
     // rows of slice k start k * Ms rows into the activation operand: the k-th launch must be slice k's
@@ -344,6 +350,7 @@ static void run_case(int arch, int p, int q, int nstreams, bool capturing, int n
                 capturing ? " capturing" : "", nlayers, parts ? " parts" : "");
   g_case = name;
   const domino_cfg c = make_cfg(arch, p, q);
+  g_rows = (long)c.batch * c.seq;
   if (domino_validate_cfg(&c) != DOMINO_OK) { EXPECT(false, "configuration rejected: %s", domino_last_error()); return; }
   Buffers B((size_t)96 << 20);
   std::vector<Layer> layers;
@@ -423,7 +430,8 @@ int main() {
         for (int ns = 1; ns <= 8; ++ns) {
           run_case(arch, p, q, ns, false, 1, false); ++cases;
           run_case(arch, p, q, ns, true, 1, false); ++cases;
-          if (q == 2) { run_case(arch, p, q, ns, false, 3, false); run_case(arch, p, q, ns, true, 3, false); cases += 2; }
+          // four blocks: the tensors handed from block to block, taken in turn, come round again
+          if (q == 2) { run_case(arch, p, q, ns, false, 4, false); run_case(arch, p, q, ns, true, 4, false); cases += 2; }
           if (q == 1) { run_case(arch, p, q, ns, false, 1, true); ++cases; }
         }
   // the check must be able to fail: two launches on different fake streams that write one buffer, no event between them
@@ -434,25 +442,25 @@ int main() {
     const int before = g_failures;
     hipStream_t a = reinterpret_cast<hipStream_t>((uintptr_t)0x1000), b = reinterpret_cast<hipStream_t>((uintptr_t)0x2000);
     hipEvent_t e;
-    hipEventCreateWithFlags(&e, 0);
-    hipEventRecord(e, a);
-    hipStreamWaitEvent(b, e, 0);
+    (void)hipEventCreateWithFlags(&e, 0);
+    (void)hipEventRecord(e, a);
+    (void)hipStreamWaitEvent(b, e, 0);
     launch(a, "writer 1", {reg(buf, 64, 8, 64, 2, true)});
     launch(b, "writer 2", {reg(buf + 64, 64, 8, 32, 2, true)});
-    hipEventRecord(e, b);
-    hipStreamWaitEvent(a, e, 0);
+    (void)hipEventRecord(e, b);
+    (void)hipStreamWaitEvent(a, e, 0);
     std::printf("(the next FAILED line is the planted race being found)\n");
     check_call(0, a, 1, false);
     if (g_failures == before + 1) g_failures = before;
     else { std::printf("the race check did not find the planted race\n"); ++g_failures; }
     // ... and two windows of one matrix that do not meet (different column ranges) are not a race
     g_ops.clear();
-    hipEventRecord(e, a);
-    hipStreamWaitEvent(b, e, 0);
+    (void)hipEventRecord(e, a);
+    (void)hipStreamWaitEvent(b, e, 0);
     launch(a, "piece 0", {reg(buf, 64, 8, 32, 2, true)});
     launch(b, "piece 1", {reg(buf + 64, 64, 8, 32, 2, true)});
-    hipEventRecord(e, b);
-    hipStreamWaitEvent(a, e, 0);
+    (void)hipEventRecord(e, b);
+    (void)hipStreamWaitEvent(a, e, 0);
     check_call(0, a, 1, false);
   }
   domino_shutdown();

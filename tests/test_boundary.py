@@ -110,6 +110,9 @@ def test_layer_calls_validate_before_touching_the_gpu():
     gs2 = domino.domino_grads(**{**full, "w_o": None})
     rc = lib.domino_layer_bwd(C.byref(c), C.byref(ps), 1, 1, 1, None, None, 1, 1, 1, C.byref(gs2), 0, 1, 1 << 40, arr, 1)
     assert rc == domino.ERR_NULL_POINTER
+    # dx must not overlap dy: a weight gradient may read dy after dx has been written
+    rc = lib.domino_layer_bwd(C.byref(c), C.byref(ps), 1, 1, 0x100000, None, None, 1, 1, 0x100100, C.byref(gs), 0, 1, 1 << 40, arr, 1)
+    assert rc == domino.ERR_INVALID_ARG and "overlaps" in domino.domino_last_error()
 
 
 def test_single_kernel_entry_points_validate():
