@@ -519,8 +519,16 @@ GradBufs grad_bufs(const Layout& L, void* ws) { return {at(ws, L.d_pre), at(ws, 
 // a chip that two slices leave half empty), so the rule follows p alone and the arithmetic does not depend on the pool.
 inline bool merged_wgrads(const Layout& L) { return L.p > 2; }
 
+// Points on a slice's stream after which the merged weight gradients, on other streams, may read what the slice has
+// written: the gradients of MLP-up's output, of the attention block's output and of q, k, v, and the slice's dx.
+struct SliceEvents {
+  hipStream_t on = nullptr;
+  hipEvent_t d_pre = nullptr, dx1 = nullptr, dqkv = nullptr, dx = nullptr;
+};
+
 int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const GradBufs& gb, hipStream_t st, hipStream_t wst,
-                      const BwdLayer& B, int i, WgChain& wg, int parts = DOMINO_BWD_ALL, hipEvent_t before_dx = nullptr) {
+                      const BwdLayer& B, int i, WgChain& wg, int parts = DOMINO_BWD_ALL, hipEvent_t before_dx = nullptr,
+                      SliceEvents* marks = nullptr) {
   const domino_params* P = B.P;
   const domino_grads* G = B.G;
   const void* saved = B.saved;
@@ -557,9 +565,10 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
 
   // the point on the slice's stream after which an operand of a weight gradient exists (only needed when the weight
   // gradients run on a stream of their own)
+  if (marks) marks->on = st;
   auto produced = [&](hipEvent_t* ev) -> int {
     *ev = nullptr;
-    if (!side) return DOMINO_OK;
+    if (!side && !marks) return DOMINO_OK;
     TRY(next_sync_event(ev));
     HIP_TRY(hipEventRecord(*ev, st), "hipEventRecord");
     return DOMINO_OK;
@@ -610,6 +619,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
   if (side) read_dy = wg.cur[0];
   hipEvent_t have_dpre;
   TRY(produced(&have_dpre));
+  if (marks) marks->d_pre = have_dpre;
   {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
     ProfScope ps(PC_DGRAD_UP, st);
     GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(B.dln2_partial, rh), L.h, Ms, L.h, L.upc);
@@ -624,6 +634,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
                dyi, dx1, AREA_G2, AREA_B2, L.llama ? -1 : AREA_BDOWN, L.llama ? -1 : AREA_BO));
   hipEvent_t have_dx1;
   TRY(produced(&have_dx1));
+  if (marks) marks->dx1 = have_dx1;
   {  // B6
     ProfScope ps(PC_DGRAD_OUT, st);
     GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
@@ -641,6 +652,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
   }
   hipEvent_t have_dqkv;
   TRY(produced(&have_dqkv));
+  if (marks) marks->dqkv = have_dqkv;
   {  // B8: input gradient of QKV: the tensor the fourth all-reduce would sum
     ProfScope ps(PC_DGRAD_QKV, st);
     GemmArgs a = gemm_args(dqkv, 3 * L.hl, P->w_qkv, 3 * L.hl, at(B.dln1_partial, rh), L.h, Ms, L.h, 3 * L.hl);
@@ -678,6 +690,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
     }
     TRY(next_sync_event(&wg.cur[4]));
     HIP_TRY(hipEventRecord(wg.cur[4], st), "hipEventRecord");
+    if (marks) marks->dx = wg.cur[4];
   }
 
   // the slice's stream ends after the slice's weight gradients: whatever follows on it (the same slice of the block
@@ -692,23 +705,30 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
 // The weight gradients of the matrices that `parts` owns, each in one launch over all rows of the block (see
 // merged_wgrads): enqueued after the slices of the block, the launches spread over the slices' streams starting at
 // streams[turn % nslice] (largest first; a stack turns the assignment from block to block so that no stream always
-// gets the big ones), after every stream's slices have got that far.  The sum over the rows runs inside the
-// kernel in a fixed order, so results are run-to-run identical.  done / done_on (4 entries, by matrix: down, up, qkv,
-// out; or NULL): an event recorded after each launch and the stream it ran on.
+// gets the big ones).  The sum over the rows runs inside the kernel in a fixed order, so results are run-to-run
+// identical.
+//   marks (one entry per slice, or NULL): with them a launch waits only for what it reads, the events the slices
+//   on other streams recorded behind the kernels that wrote its operand (all long past when a stream has finished
+//   its own slice, so the launches start without a stall and fill the time in which the slowest slice finishes);
+//   `above`: the marks of the block above in a stack, whose slices wrote this block's dy.  Without marks the
+//   streams meet on streams[0] and part again first, the same join and fork that end one call and begin the next:
+//   the form for a call under HIP graph capture (a graph captured with direct waits of every stream for every
+//   other one crashed the runtime when it was instantiated).
+//   done / done_on (4 entries, by matrix: down, up, qkv, out; or NULL): an event recorded after each launch and the
+//   stream it ran on.
 int enqueue_merged_wgrads(const Layout& L, const StreamPlan& S, const GradBufs& gb, const BwdLayer& B, int parts, int turn,
+                          const std::vector<SliceEvents>* marks, const std::vector<SliceEvents>* above = nullptr,
                           hipEvent_t* done = nullptr, hipStream_t* done_on = nullptr) {
   const char* sv = static_cast<const char*>(B.saved);
   const domino_grads* G = B.G;
-  struct { int part, cls; const void* A; long lda; const void* Bm; long ldb; float* C; long ldc; int M, N; } w[4] = {
-    {DOMINO_BWD_MLP, PC_WGRAD_DOWN, sv + L.act, L.fl, B.dy, L.h, G->w_down, L.h, L.fl, L.h},
-    {DOMINO_BWD_MLP, PC_WGRAD_UP, sv + L.ln2, L.h, gb.d_pre, L.upc, G->w_up, L.upc, L.h, L.upc},
-    {DOMINO_BWD_ATTN, PC_WGRAD_QKV, sv + L.ln1, L.h, gb.dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl},
-    {DOMINO_BWD_ATTN, PC_WGRAD_OUT, sv + L.ctx, L.hl, gb.dx1, L.h, G->w_o, L.h, L.hl, L.h}};
+  enum { OP_DY, OP_DPRE, OP_DQKV, OP_DX1 };
+  struct { int part, cls, operand; const void* A; long lda; const void* Bm; long ldb; float* C; long ldc; int M, N; } w[4] = {
+    {DOMINO_BWD_MLP, PC_WGRAD_DOWN, OP_DY, sv + L.act, L.fl, B.dy, L.h, G->w_down, L.h, L.fl, L.h},
+    {DOMINO_BWD_MLP, PC_WGRAD_UP, OP_DPRE, sv + L.ln2, L.h, gb.d_pre, L.upc, G->w_up, L.upc, L.h, L.upc},
+    {DOMINO_BWD_ATTN, PC_WGRAD_QKV, OP_DQKV, sv + L.ln1, L.h, gb.dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl},
+    {DOMINO_BWD_ATTN, PC_WGRAD_OUT, OP_DX1, sv + L.ctx, L.hl, gb.dx1, L.h, G->w_o, L.h, L.hl, L.h}};
   if (!(parts & (DOMINO_BWD_MLP | DOMINO_BWD_ATTN))) return DOMINO_OK;
-  // every stream's slices must have got this far: the streams meet on streams[0] and part again, the same join and
-  // fork that end one call and begin the next (direct waits of every stream for every other one say the same with
-  // more edges, but a HIP graph captured with them crashed the runtime when it was instantiated)
-  if (S.nslice > 1) {
+  if (!marks && S.nslice > 1) {
     const std::vector<char> slices = S.used(false);
     TRY(join_streams(S, slices));
     TRY(fork_streams(S, slices));
@@ -717,6 +737,14 @@ int enqueue_merged_wgrads(const Layout& L, const StreamPlan& S, const GradBufs& 
   for (int m = 0; m < 4; ++m) {
     if (!(parts & w[m].part)) continue;
     hipStream_t st = S.slice((slot++ + turn) % S.nslice);
+    if (marks) {
+      const std::vector<SliceEvents>* from = w[m].operand == OP_DY ? above : marks;     // dy of a single block is the caller's
+      if (from)
+        for (const SliceEvents& e : *from) {
+          hipEvent_t ev = w[m].operand == OP_DY ? e.dx : w[m].operand == OP_DPRE ? e.d_pre : w[m].operand == OP_DQKV ? e.dqkv : e.dx1;
+          if (ev && e.on != st) HIP_TRY(hipStreamWaitEvent(st, ev, 0), "hipStreamWaitEvent");
+        }
+    }
     {
       ProfScope ps(w[m].cls, st);
       GemmArgs a = gemm_args(w[m].A, w[m].lda, w[m].Bm, w[m].ldb, w[m].C, w[m].ldc, w[m].M, w[m].N, L.M);
@@ -868,8 +896,11 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   TRY(fork_streams(S, used));
   WgChain wg;
   const GradBufs gb = grad_bufs(L, workspace);
-  for (int i = 0; i < L.p; ++i) TRY(enqueue_bwd_slice(L, cfg, workspace, gb, S.slice(i), S.second(i), B, i, wg, parts));
-  if (merged_wgrads(L)) TRY(enqueue_merged_wgrads(L, S, gb, B, parts, 0));
+  const bool merged = merged_wgrads(L);
+  std::vector<SliceEvents> marks(merged && !g_capturing ? L.p : 0);
+  for (int i = 0; i < L.p; ++i)
+    TRY(enqueue_bwd_slice(L, cfg, workspace, gb, S.slice(i), S.second(i), B, i, wg, parts, nullptr, marks.empty() ? nullptr : &marks[i]));
+  if (merged) TRY(enqueue_merged_wgrads(L, S, gb, B, parts, 0, marks.empty() ? nullptr : &marks));
   TRY(join_streams(S, used));
   return DOMINO_OK;
 }
@@ -951,6 +982,7 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   // merged weight gradients of the last block that used each set of gradient tensors: by matrix (down, up, qkv, out)
   hipEvent_t wdone[2][4] = {};
   hipStream_t won[2][4] = {};
+  std::vector<SliceEvents> marks[2];       // of the current block and of the block above
   for (int l = nlayers - 1; l >= 0; --l) {
     const int turn = (nlayers - 1 - l) & 1;
     if (merged) {
@@ -963,9 +995,14 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
     WgChain wg;
     // dx of this block goes where the block above read its dy: its down-projection weight gradient must be through
     hipEvent_t before_dx = merged ? wdone[turn ^ 1][0] : nullptr;
+    std::vector<SliceEvents>& mk = marks[turn];
+    mk.assign(merged && !g_capturing ? L.p : 0, SliceEvents{});
     for (int i = 0; i < L.p; ++i)
-      TRY(enqueue_bwd_slice(L, cfg, workspace, gb[turn], S.slice(i), S.second(i), layers[l], i, wg, DOMINO_BWD_ALL, before_dx));
-    if (merged) TRY(enqueue_merged_wgrads(L, S, gb[turn], layers[l], DOMINO_BWD_ALL, nlayers - 1 - l, wdone[turn], won[turn]));
+      TRY(enqueue_bwd_slice(L, cfg, workspace, gb[turn], S.slice(i), S.second(i), layers[l], i, wg, DOMINO_BWD_ALL, before_dx,
+                            mk.empty() ? nullptr : &mk[i]));
+    if (merged)
+      TRY(enqueue_merged_wgrads(L, S, gb[turn], layers[l], DOMINO_BWD_ALL, nlayers - 1 - l, mk.empty() ? nullptr : &mk,
+                                l + 1 < nlayers && !marks[turn ^ 1].empty() ? &marks[turn ^ 1] : nullptr, wdone[turn], won[turn]));
   }
   TRY(join_streams(S, used));
   return DOMINO_OK;
