@@ -512,12 +512,31 @@ struct GradBufs { char *d_pre, *dx1, *dqkv; };
 GradBufs grad_bufs(const Layout& L, void* ws) { return {at(ws, L.d_pre), at(ws, L.dx1), at(ws, L.dqkv)}; }
 
 // With more than two row slices the weight gradients are not formed slice by slice: one launch per matrix contracts
-// over all rows of the block after the last slice's input gradients (enqueue_merged_wgrads).  Slice by slice, every
+// over all rows of the block after the last slice's input gradients (enqueue_block_end).  Slice by slice, every
 // slice after the first reads and rewrites the whole fp32 gradient (for the 13B shard 0.94 GB of 9.4 GB per step at
 // p = 4) in launches a quarter as deep; the step sits on the board's power cap, so the saved traffic is saved time
 // (3.5-4.5 % of the step).  With one or two slices the slice-by-slice launches on second streams are faster (they fill
 // a chip that two slices leave half empty), so the rule follows p alone and the arithmetic does not depend on the pool.
 inline bool merged_wgrads(const Layout& L) { return L.p > 2; }
+
+// out (+)= the partial rows that `nslices` consecutive slices, the first one's block of partial sums at `red`, left for
+// the eight vector gradients (norm gains and shifts, biases): one launch, slices and rows summed in index order
+int vector_grads(const Layout& L, const BwdLayer& B, const float* red, int nslices, int accumulate, hipStream_t st) {
+  const domino_grads* G = B.G;
+  ProfScope ps(PC_COLSUM, st);
+  struct { int k; float* out; } vec[NAREAS] = {
+    {AREA_G1, G->norm1_g}, {AREA_B1, G->norm1_b}, {AREA_G2, G->norm2_g}, {AREA_B2, G->norm2_b},
+    {AREA_BQKV, G->b_qkv}, {AREA_BO, G->b_o}, {AREA_BUP, G->b_up}, {AREA_BDOWN, G->b_down}};
+  ColsumJobs jobs{};
+  int njobs = 0;
+  for (auto& v : vec) {
+    if (!v.out) continue;
+    if (L.llama && v.k != AREA_G1 && v.k != AREA_G2) continue;
+    jobs.job[njobs++] = {red + L.area_off[v.k], v.out, L.area_rows[v.k], L.area_n[v.k], (long)L.area_n[v.k], nslices, (long)L.red_floats};
+  }
+  LAUNCH(colsum_finish_jobs_launch(jobs, njobs, accumulate, st), "vector gradient reduction");
+  return DOMINO_OK;
+}
 
 // Points on a slice's stream after which the merged weight gradients, on other streams, may read what the slice has
 // written: the gradients of MLP-up's output, of the attention block's output and of q, k, v, and the slice's dx.
@@ -670,27 +689,18 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
     if (before_dx) HIP_TRY(hipStreamWaitEvent(st, before_dx, 0), "hipStreamWaitEvent");
     TRY(norm_bwd(at(B.dln1_partial, rh), B.dln1_others ? at(B.dln1_others, rh) : nullptr, xi, P->norm1_g, mean1, rstd1,
                  dx1, at(B.dx, rh), AREA_G1, AREA_B1));
-    // Vector gradients (norm gains and shifts, biases): the partial rows of all three parts of this slice lie in
-    // its block of the workspace now; one launch adds them to the gradients, after slice i-1's launch did
-    // (fixed order), so only the last slice's small sum is left at the end of the block.
-    if (chain) HIP_TRY(hipStreamWaitEvent(st, wg.done[4], 0), "hipStreamWaitEvent");
-    {
-      ProfScope ps(PC_COLSUM, st);
-      struct { int k; float* out; } vec[NAREAS] = {
-        {AREA_G1, G->norm1_g}, {AREA_B1, G->norm1_b}, {AREA_G2, G->norm2_g}, {AREA_B2, G->norm2_b},
-        {AREA_BQKV, G->b_qkv}, {AREA_BO, G->b_o}, {AREA_BUP, G->b_up}, {AREA_BDOWN, G->b_down}};
-      ColsumJobs jobs{};
-      int njobs = 0;
-      for (auto& v : vec) {
-        if (!v.out) continue;
-        if (L.llama && v.k != AREA_G1 && v.k != AREA_G2) continue;
-        jobs.job[njobs++] = {area(v.k), v.out, L.area_rows[v.k], L.area_n[v.k], (long)L.area_n[v.k], 1, 0L};
-      }
-      LAUNCH(colsum_finish_jobs_launch(jobs, njobs, beta, st), "vector gradient reduction");
+    if (merged) {
+      // the vector gradients are summed over all slices in one launch at the end of the block (enqueue_block_end)
+      if (marks) TRY(produced(&marks->dx));
+    } else {
+      // Vector gradients (norm gains and shifts, biases): the partial rows of all three parts of this slice lie in
+      // its block of the workspace now; one launch adds them to the gradients, after slice i-1's launch did
+      // (fixed order), so only the last slice's small sum is left at the end of the block.
+      if (chain) HIP_TRY(hipStreamWaitEvent(st, wg.done[4], 0), "hipStreamWaitEvent");
+      TRY(vector_grads(L, B, red, 1, beta, st));
+      TRY(next_sync_event(&wg.cur[4]));
+      HIP_TRY(hipEventRecord(wg.cur[4], st), "hipEventRecord");
     }
-    TRY(next_sync_event(&wg.cur[4]));
-    HIP_TRY(hipEventRecord(wg.cur[4], st), "hipEventRecord");
-    if (marks) marks->dx = wg.cur[4];
   }
 
   // the slice's stream ends after the slice's weight gradients: whatever follows on it (the same slice of the block
@@ -702,8 +712,9 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
   return DOMINO_OK;
 }
 
-// The weight gradients of the matrices that `parts` owns, each in one launch over all rows of the block (see
-// merged_wgrads): enqueued after the slices of the block, the launches spread over the slices' streams starting at
+// The end of a block whose weight gradients are merged (see merged_wgrads): the weight gradients of the matrices that
+// `parts` owns, each in one launch over all rows of the block, and (with the Norm1 part) one launch that sums the
+// vector gradients over all slices.  Enqueued after the slices of the block, the launches spread over the slices' streams starting at
 // streams[turn % nslice] (largest first; a stack turns the assignment from block to block so that no stream always
 // gets the big ones).  The sum over the rows runs inside the kernel in a fixed order, so results are run-to-run
 // identical.
@@ -716,7 +727,7 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
 //   other one crashed the runtime when it was instantiated).
 //   done / done_on (4 entries, by matrix: down, up, qkv, out; or NULL): an event recorded after each launch and the
 //   stream it ran on.
-int enqueue_merged_wgrads(const Layout& L, const StreamPlan& S, const GradBufs& gb, const BwdLayer& B, int parts, int turn,
+int enqueue_block_end(const Layout& L, const StreamPlan& S, const GradBufs& gb, const BwdLayer& B, int parts, int turn,
                           const std::vector<SliceEvents>* marks, const std::vector<SliceEvents>* above = nullptr,
                           hipEvent_t* done = nullptr, hipStream_t* done_on = nullptr) {
   const char* sv = static_cast<const char*>(B.saved);
@@ -727,7 +738,6 @@ int enqueue_merged_wgrads(const Layout& L, const StreamPlan& S, const GradBufs& 
     {DOMINO_BWD_MLP, PC_WGRAD_UP, OP_DPRE, sv + L.ln2, L.h, gb.d_pre, L.upc, G->w_up, L.upc, L.h, L.upc},
     {DOMINO_BWD_ATTN, PC_WGRAD_QKV, OP_DQKV, sv + L.ln1, L.h, gb.dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl},
     {DOMINO_BWD_ATTN, PC_WGRAD_OUT, OP_DX1, sv + L.ctx, L.hl, gb.dx1, L.h, G->w_o, L.h, L.hl, L.h}};
-  if (!(parts & (DOMINO_BWD_MLP | DOMINO_BWD_ATTN))) return DOMINO_OK;
   if (!marks && S.nslice > 1) {
     const std::vector<char> slices = S.used(false);
     TRY(join_streams(S, slices));
@@ -756,6 +766,15 @@ int enqueue_merged_wgrads(const Layout& L, const StreamPlan& S, const GradBufs& 
       HIP_TRY(hipEventRecord(done[m], st), "hipEventRecord");
       done_on[m] = st;
     }
+  }
+  if (parts & DOMINO_BWD_NORM1) {
+    // the eight vector gradients from the partial rows of all slices, behind the smallest weight gradient: by the
+    // time that stream gets here the last slice's Norm1 backward, whose partial rows it needs, is through
+    hipStream_t st = S.slice((3 + turn) % S.nslice);
+    if (marks)
+      for (const SliceEvents& e : *marks)
+        if (e.dx && e.on != st) HIP_TRY(hipStreamWaitEvent(st, e.dx, 0), "hipStreamWaitEvent");
+    TRY(vector_grads(L, B, B.red, L.p, B.accumulate ? 1 : 0, st));
   }
   return DOMINO_OK;
 }
@@ -900,7 +919,7 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   std::vector<SliceEvents> marks(merged && !g_capturing ? L.p : 0);
   for (int i = 0; i < L.p; ++i)
     TRY(enqueue_bwd_slice(L, cfg, workspace, gb, S.slice(i), S.second(i), B, i, wg, parts, nullptr, marks.empty() ? nullptr : &marks[i]));
-  if (merged) TRY(enqueue_merged_wgrads(L, S, gb, B, parts, 0, marks.empty() ? nullptr : &marks));
+  if (merged) TRY(enqueue_block_end(L, S, gb, B, parts, 0, marks.empty() ? nullptr : &marks));
   TRY(join_streams(S, used));
   return DOMINO_OK;
 }
@@ -1001,7 +1020,7 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
       TRY(enqueue_bwd_slice(L, cfg, workspace, gb[turn], S.slice(i), S.second(i), layers[l], i, wg, DOMINO_BWD_ALL, before_dx,
                             mk.empty() ? nullptr : &mk[i]));
     if (merged)
-      TRY(enqueue_merged_wgrads(L, S, gb[turn], layers[l], DOMINO_BWD_ALL, nlayers - 1 - l, mk.empty() ? nullptr : &mk,
+      TRY(enqueue_block_end(L, S, gb[turn], layers[l], DOMINO_BWD_ALL, nlayers - 1 - l, mk.empty() ? nullptr : &mk,
                                 l + 1 < nlayers && !marks[turn ^ 1].empty() ? &marks[turn ^ 1] : nullptr, wdone[turn], won[turn]));
   }
   TRY(join_streams(S, used));
