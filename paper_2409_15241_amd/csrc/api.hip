@@ -503,6 +503,12 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
 struct WgChain {
   hipStream_t prev = nullptr, prev_w = nullptr;      // the previous slice's stream and weight-gradient stream
   hipEvent_t done[5] = {}, cur[5] = {};
+  // the next slice of the block runs on other streams and will wait for this slice's sums: only then are the events
+  // behind them recorded (a record between two kernels costs a few microseconds on the stream)
+  bool feeds_next = true;
+  void next_is(const StreamPlan& S, int i, int p) {
+    feeds_next = i + 1 < p && (S.slice(i + 1) != S.slice(i) || S.second(i + 1) != S.second(i));
+  }
 };
 
 // Backward of row slice i of one block; within the slice each input gradient is enqueued before the weight
@@ -538,11 +544,13 @@ int vector_grads(const Layout& L, const BwdLayer& B, const float* red, int nslic
   return DOMINO_OK;
 }
 
-// Points on a slice's stream after which the merged weight gradients, on other streams, may read what the slice has
-// written: the gradients of MLP-up's output, of the attention block's output and of q, k, v, and the slice's dx.
+// Points on a slice's stream after which the merged launches at the end of the block, on other streams, may read what
+// the slice has written: `ready` behind the last kernel of the call that writes an operand of a weight gradient (the
+// attention backward, which leaves the gradient of q, k, v; in a call of the MLP part alone the down-projection's input
+// gradient), `dx` behind the Norm1 backward.  One record each: a record between two kernels costs a few microseconds.
 struct SliceEvents {
   hipStream_t on = nullptr;
-  hipEvent_t d_pre = nullptr, dx1 = nullptr, dqkv = nullptr, dx = nullptr;
+  hipEvent_t ready = nullptr, dx = nullptr;
 };
 
 int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const GradBufs& gb, hipStream_t st, hipStream_t wst,
@@ -581,13 +589,14 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
   const bool chain_w = wg.prev_w && wg.prev_w != wst;
   const bool side = wst != st;
   const bool merged = merged_wgrads(L);
+  for (hipEvent_t& e : wg.cur) e = nullptr;
 
   // the point on the slice's stream after which an operand of a weight gradient exists (only needed when the weight
   // gradients run on a stream of their own)
   if (marks) marks->on = st;
   auto produced = [&](hipEvent_t* ev) -> int {
     *ev = nullptr;
-    if (!side && !marks) return DOMINO_OK;
+    if (!side) return DOMINO_OK;
     TRY(next_sync_event(ev));
     HIP_TRY(hipEventRecord(*ev, st), "hipEventRecord");
     return DOMINO_OK;
@@ -603,8 +612,10 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
       a.beta = beta;
       LAUNCH(gemm_launch(GEMM_TN, EPI_ACC_F32, a, -1, wst), "weight gradient");
     }
-    TRY(next_sync_event(&wg.cur[which]));
-    HIP_TRY(hipEventRecord(wg.cur[which], wst), "hipEventRecord");
+    if (wg.feeds_next || (side && which == 0)) {       // (the second stream's reader of dy is waited for below)
+      TRY(next_sync_event(&wg.cur[which]));
+      HIP_TRY(hipEventRecord(wg.cur[which], wst), "hipEventRecord");
+    }
     return DOMINO_OK;
   };
   auto colsum = [&](const void* g, long ld, int n, int k) -> int {
@@ -638,7 +649,10 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
   if (side) read_dy = wg.cur[0];
   hipEvent_t have_dpre;
   TRY(produced(&have_dpre));
-  if (marks) marks->d_pre = have_dpre;
+  if (marks && !(parts & DOMINO_BWD_ATTN)) {
+    TRY(next_sync_event(&marks->ready));
+    HIP_TRY(hipEventRecord(marks->ready, st), "hipEventRecord");
+  }
   {  // B4: input gradient of MLP-up: the tensor the third all-reduce would sum
     ProfScope ps(PC_DGRAD_UP, st);
     GemmArgs a = gemm_args(d_pre, L.upc, P->w_up, L.upc, at(B.dln2_partial, rh), L.h, Ms, L.h, L.upc);
@@ -653,7 +667,6 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
                dyi, dx1, AREA_G2, AREA_B2, L.llama ? -1 : AREA_BDOWN, L.llama ? -1 : AREA_BO));
   hipEvent_t have_dx1;
   TRY(produced(&have_dx1));
-  if (marks) marks->dx1 = have_dx1;
   {  // B6
     ProfScope ps(PC_DGRAD_OUT, st);
     GemmArgs a = gemm_args(dx1, L.h, P->w_o, L.h, dctx, L.hl, Ms, L.hl, L.h);
@@ -671,7 +684,10 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
   }
   hipEvent_t have_dqkv;
   TRY(produced(&have_dqkv));
-  if (marks) marks->dqkv = have_dqkv;
+  if (marks) {
+    TRY(next_sync_event(&marks->ready));
+    HIP_TRY(hipEventRecord(marks->ready, st), "hipEventRecord");
+  }
   {  // B8: input gradient of QKV: the tensor the fourth all-reduce would sum
     ProfScope ps(PC_DGRAD_QKV, st);
     GemmArgs a = gemm_args(dqkv, 3 * L.hl, P->w_qkv, 3 * L.hl, at(B.dln1_partial, rh), L.h, Ms, L.h, 3 * L.hl);
@@ -691,15 +707,20 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
                  dx1, at(B.dx, rh), AREA_G1, AREA_B1));
     if (merged) {
       // the vector gradients are summed over all slices in one launch at the end of the block (enqueue_block_end)
-      if (marks) TRY(produced(&marks->dx));
+      if (marks) {
+        TRY(next_sync_event(&marks->dx));
+        HIP_TRY(hipEventRecord(marks->dx, st), "hipEventRecord");
+      }
     } else {
       // Vector gradients (norm gains and shifts, biases): the partial rows of all three parts of this slice lie in
       // its block of the workspace now; one launch adds them to the gradients, after slice i-1's launch did
       // (fixed order), so only the last slice's small sum is left at the end of the block.
       if (chain) HIP_TRY(hipStreamWaitEvent(st, wg.done[4], 0), "hipStreamWaitEvent");
       TRY(vector_grads(L, B, red, 1, beta, st));
-      TRY(next_sync_event(&wg.cur[4]));
-      HIP_TRY(hipEventRecord(wg.cur[4], st), "hipEventRecord");
+      if (wg.feeds_next) {
+        TRY(next_sync_event(&wg.cur[4]));
+        HIP_TRY(hipEventRecord(wg.cur[4], st), "hipEventRecord");
+      }
     }
   }
 
@@ -718,9 +739,10 @@ int enqueue_bwd_slice(const Layout& L, const domino_cfg* cfg, void* ws, const Gr
 // streams[turn % nslice] (largest first; a stack turns the assignment from block to block so that no stream always
 // gets the big ones).  The sum over the rows runs inside the kernel in a fixed order, so results are run-to-run
 // identical.
-//   marks (one entry per slice, or NULL): with them a launch waits only for what it reads, the events the slices
-//   on other streams recorded behind the kernels that wrote its operand (all long past when a stream has finished
-//   its own slice, so the launches start without a stall and fill the time in which the slowest slice finishes);
+//   marks (one entry per slice, or NULL): with them a launch waits only for the events that the slices on other
+//   streams recorded behind the last kernel that writes an operand of a weight gradient (long past when a stream
+//   has finished its own slice, so the launches start without a stall and fill the time in which the slowest slice
+//   finishes);
 //   `above`: the marks of the block above in a stack, whose slices wrote this block's dy.  Without marks the
 //   streams meet on streams[0] and part again first, the same join and fork that end one call and begin the next:
 //   the form for a call under HIP graph capture (a graph captured with direct waits of every stream for every
@@ -751,7 +773,7 @@ int enqueue_block_end(const Layout& L, const StreamPlan& S, const GradBufs& gb, 
       const std::vector<SliceEvents>* from = w[m].operand == OP_DY ? above : marks;     // dy of a single block is the caller's
       if (from)
         for (const SliceEvents& e : *from) {
-          hipEvent_t ev = w[m].operand == OP_DY ? e.dx : w[m].operand == OP_DPRE ? e.d_pre : w[m].operand == OP_DQKV ? e.dqkv : e.dx1;
+          hipEvent_t ev = w[m].operand == OP_DY ? e.dx : e.ready;
           if (ev && e.on != st) HIP_TRY(hipStreamWaitEvent(st, ev, 0), "hipStreamWaitEvent");
         }
     }
@@ -917,8 +939,10 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   const GradBufs gb = grad_bufs(L, workspace);
   const bool merged = merged_wgrads(L);
   std::vector<SliceEvents> marks(merged && !g_capturing ? L.p : 0);
-  for (int i = 0; i < L.p; ++i)
+  for (int i = 0; i < L.p; ++i) {
+    wg.next_is(S, i, L.p);
     TRY(enqueue_bwd_slice(L, cfg, workspace, gb, S.slice(i), S.second(i), B, i, wg, parts, nullptr, marks.empty() ? nullptr : &marks[i]));
+  }
   if (merged) TRY(enqueue_block_end(L, S, gb, B, parts, 0, marks.empty() ? nullptr : &marks));
   TRY(join_streams(S, used));
   return DOMINO_OK;
@@ -1016,9 +1040,11 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
     hipEvent_t before_dx = merged ? wdone[turn ^ 1][0] : nullptr;
     std::vector<SliceEvents>& mk = marks[turn];
     mk.assign(merged && !g_capturing ? L.p : 0, SliceEvents{});
-    for (int i = 0; i < L.p; ++i)
+    for (int i = 0; i < L.p; ++i) {
+      wg.next_is(S, i, L.p);
       TRY(enqueue_bwd_slice(L, cfg, workspace, gb[turn], S.slice(i), S.second(i), layers[l], i, wg, DOMINO_BWD_ALL, before_dx,
                             mk.empty() ? nullptr : &mk[i]));
+    }
     if (merged)
       TRY(enqueue_block_end(L, S, gb[turn], layers[l], DOMINO_BWD_ALL, nlayers - 1 - l, mk.empty() ? nullptr : &mk,
                                 l + 1 < nlayers && !marks[turn ^ 1].empty() ? &marks[turn ^ 1] : nullptr, wdone[turn], won[turn]));
