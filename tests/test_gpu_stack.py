@@ -64,7 +64,10 @@ def run_layer_by_layer(H, sc, params, others, x, dy, nstreams):
 
 @pytest.mark.parametrize("base,nlayers,p,q,nstreams", [
     ("tiny", 3, 2, 2, 4), ("tiny", 2, 4, 2, 8), ("tiny", 2, 4, 1, 2), ("tiny-llama", 3, 2, 2, 4),
-    ("tiny-llama", 2, 1, 4, 1)])
+    ("tiny-llama", 2, 1, 4, 1),
+    # more than two slices: the weight gradients of a block are one launch per matrix over all rows, and from the third
+    # block on the tensors those launches read, kept twice and used in turn, come round again
+    ("tiny", 5, 4, 2, 4), ("tiny-llama", 4, 4, 2, 4), ("tiny", 4, 4, 1, 3), ("tiny", 3, 4, 2, 1)])
 def test_stack_is_bitwise_the_blocks_called_one_by_one(H, base, nlayers, p, q, nstreams):
     from paper_2409_15241_amd import domino
     sc = synth.WORKLOADS[base].replace(p=p, q=q, batch=4)
@@ -136,11 +139,40 @@ def test_stack_accumulates_and_repeats_bitwise(H):
                 assert float((G1[k] - 2 * g).abs().max()) <= 1e-5 * float(g.abs().max()), k
 
 
+def test_deep_stack_of_mid_size_blocks_repeats_bitwise(H):
+    """Five blocks of a shape whose kernels take long enough to overlap across streams, four slices on four streams:
+    ten passes over the same buffers leave the bits of the first, and those are the bits of the blocks called one by
+    one.  (A launch that read a tensor while the block two below already overwrote it would show here.)"""
+    sc = synth.ShardConfig("mid-gpt-d64-stack", 1024, 16, 2, 0, 4, 2, 4, 256, 4096, synth.ARCH_GPT, index=15)
+    nlayers = 5
+    params, others = synth.make_stack(sc, nlayers, random_affine=True)
+    x, dy = synth.make_activations(sc)
+    st = run_stack(H, sc, params, others, x, dy, 4)
+    first = [{k: (None if g is None else g.clone()) for k, g in G.items()} for G in st.grads]
+    dx = st.dx.clone()
+    for rep in range(10):
+        st.forward()
+        st.backward()
+        st.sync()
+        assert torch.equal(dx, st.dx), rep
+        for l, (G0, G1) in enumerate(zip(first, st.grads)):
+            for k, g in G0.items():
+                if g is not None:
+                    assert torch.equal(g, G1[k]), (rep, l, k)
+    bufs = run_layer_by_layer(H, sc, params, others, x, dy, 4)
+    for l, b in enumerate(bufs):
+        for k, g in b.grads.items():
+            if g is not None:
+                assert torch.equal(first[l][k], g), (l, k)
+    assert torch.equal(dx, bufs[0].dx)
+
+
 @pytest.mark.parametrize("name", ["gpt3-13b", "llama2-7b"])
 def test_full_size_stack_matches_single_blocks_bitwise(H, name):
-    """The benchmark's shard (GPT-3 13B, p=4, q=2, 4 streams) and a Llama shard (p=2, q=4), two blocks."""
+    """The benchmark's shard (GPT-3 13B, p=4, q=2, 4 streams; four blocks, so that the tensors its merged weight
+    gradients read come round again) and a Llama shard (p=2, q=4; two blocks)."""
     sc = synth.WORKLOADS[name]
-    params, others = synth.make_stack(sc, 2)
+    params, others = synth.make_stack(sc, 4 if sc.p > 2 else 2)
     x, dy = synth.make_activations(sc)
     st = run_stack(H, sc, params, others, x, dy, 4)
     bufs = run_layer_by_layer(H, sc, params, others, x, dy, 4)
