@@ -498,8 +498,9 @@ int enqueue_fwd_slice(const Layout& L, const domino_cfg* cfg, const StreamPlan& 
   return DOMINO_OK;
 }
 
-// Weight gradients are summed over the row slices in slice order: slice i's product into a matrix waits for
-// slice i-1's product into the same matrix (one event per matrix; the fifth is for the vector gradients).
+// With one or two row slices (see merged_wgrads for more) the weight gradients are summed over the slices in slice
+// order: slice i's product into a matrix waits for slice i-1's product into the same matrix (one event per matrix; the
+// fifth is for the vector gradients).
 struct WgChain {
   hipStream_t prev = nullptr, prev_w = nullptr;      // the previous slice's stream and weight-gradient stream
   hipEvent_t done[5] = {}, cur[5] = {};
