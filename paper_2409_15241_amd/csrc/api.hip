@@ -755,12 +755,12 @@ int enqueue_block_end(const Layout& L, const StreamPlan& S, const GradBufs& gb, 
                           hipEvent_t* done = nullptr, hipStream_t* done_on = nullptr) {
   const char* sv = static_cast<const char*>(B.saved);
   const domino_grads* G = B.G;
-  enum { OP_DY, OP_DPRE, OP_DQKV, OP_DX1 };
-  struct { int part, cls, operand; const void* A; long lda; const void* Bm; long ldb; float* C; long ldc; int M, N; } w[4] = {
-    {DOMINO_BWD_MLP, PC_WGRAD_DOWN, OP_DY, sv + L.act, L.fl, B.dy, L.h, G->w_down, L.h, L.fl, L.h},
-    {DOMINO_BWD_MLP, PC_WGRAD_UP, OP_DPRE, sv + L.ln2, L.h, gb.d_pre, L.upc, G->w_up, L.upc, L.h, L.upc},
-    {DOMINO_BWD_ATTN, PC_WGRAD_QKV, OP_DQKV, sv + L.ln1, L.h, gb.dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl},
-    {DOMINO_BWD_ATTN, PC_WGRAD_OUT, OP_DX1, sv + L.ctx, L.hl, gb.dx1, L.h, G->w_o, L.h, L.hl, L.h}};
+  // second operand: dy (written by the block above, or the caller's) for the down-projection, else a tensor of this block's slices
+  struct { int part, cls; bool reads_dy; const void* A; long lda; const void* Bm; long ldb; float* C; long ldc; int M, N; } w[4] = {
+    {DOMINO_BWD_MLP, PC_WGRAD_DOWN, true, sv + L.act, L.fl, B.dy, L.h, G->w_down, L.h, L.fl, L.h},
+    {DOMINO_BWD_MLP, PC_WGRAD_UP, false, sv + L.ln2, L.h, gb.d_pre, L.upc, G->w_up, L.upc, L.h, L.upc},
+    {DOMINO_BWD_ATTN, PC_WGRAD_QKV, false, sv + L.ln1, L.h, gb.dqkv, 3 * L.hl, G->w_qkv, 3 * L.hl, L.h, 3 * L.hl},
+    {DOMINO_BWD_ATTN, PC_WGRAD_OUT, false, sv + L.ctx, L.hl, gb.dx1, L.h, G->w_o, L.h, L.hl, L.h}};
   if (!marks && S.nslice > 1) {
     const std::vector<char> slices = S.used(false);
     TRY(join_streams(S, slices));
@@ -771,10 +771,10 @@ int enqueue_block_end(const Layout& L, const StreamPlan& S, const GradBufs& gb, 
     if (!(parts & w[m].part)) continue;
     hipStream_t st = S.slice((slot++ + turn) % S.nslice);
     if (marks) {
-      const std::vector<SliceEvents>* from = w[m].operand == OP_DY ? above : marks;     // dy of a single block is the caller's
+      const std::vector<SliceEvents>* from = w[m].reads_dy ? above : marks;     // dy of a single block is the caller's
       if (from)
         for (const SliceEvents& e : *from) {
-          hipEvent_t ev = w[m].operand == OP_DY ? e.dx : e.ready;
+          hipEvent_t ev = w[m].reads_dy ? e.dx : e.ready;
           if (ev && e.on != st) HIP_TRY(hipStreamWaitEvent(st, ev, 0), "hipStreamWaitEvent");
         }
     }
