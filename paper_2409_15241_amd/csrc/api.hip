@@ -939,7 +939,7 @@ int domino_layer_bwd_parts(const domino_cfg* cfg, const domino_params* P, const 
   WgChain wg;
   const GradBufs gb = grad_bufs(L, workspace);
   const bool merged = merged_wgrads(L);
-  std::vector<SliceEvents> marks(merged && !g_capturing ? L.p : 0);
+  std::vector<SliceEvents> marks(merged && !g_capturing && S.nslice > 1 ? L.p : 0);     // (one stream orders itself)
   for (int i = 0; i < L.p; ++i) {
     wg.next_is(S, i, L.p);
     TRY(enqueue_bwd_slice(L, cfg, workspace, gb, S.slice(i), S.second(i), B, i, wg, parts, nullptr, marks.empty() ? nullptr : &marks[i]));
@@ -1040,7 +1040,7 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
     // dx of this block goes where the block above read its dy: its down-projection weight gradient must be through
     hipEvent_t before_dx = merged ? wdone[turn ^ 1][0] : nullptr;
     std::vector<SliceEvents>& mk = marks[turn];
-    mk.assign(merged && !g_capturing ? L.p : 0, SliceEvents{});
+    mk.assign(merged && !g_capturing && S.nslice > 1 ? L.p : 0, SliceEvents{});
     for (int i = 0; i < L.p; ++i) {
       wg.next_is(S, i, L.p);
       TRY(enqueue_bwd_slice(L, cfg, workspace, gb[turn], S.slice(i), S.second(i), layers[l], i, wg, DOMINO_BWD_ALL, before_dx,
