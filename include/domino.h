@@ -202,7 +202,9 @@ int domino_stack_fwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
  * For p <= 2 a slice goes on from block to block without waiting for the others; for p > 2 the slices of a block
  * meet before its weight gradients (one launch per matrix over all rows), after which each stream goes on with
  * its slice of the block below while the other streams' launches still run (the tensors those read are kept
- * twice and used in turn).  Results are bitwise those of nlayers calls of domino_layer_bwd. */
+ * twice and used in turn).  Results are bitwise those of nlayers calls of domino_layer_bwd.
+ * Under HIP graph capture (see domino_layer_fwd) a stack backward of more than one block with p > 2 returns
+ * DOMINO_ERR_UNSUPPORTED before anything is enqueued: capture one domino_layer_bwd call per block instead. */
 int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* params, const void* dy,
                      const domino_stack_bwd_io* io, void* dx, const domino_grads* grads, int accumulate,
                      void* workspace, size_t workspace_bytes, void* const* streams, int nstreams);

@@ -1017,10 +1017,16 @@ int domino_stack_bwd(const domino_cfg* cfg, int nlayers, const domino_params* pa
   TRY(begin_call(streams, nstreams, L.p, true));
   ConcurrencyScope conc(StreamPlan(streams, nstreams, L.p).in_flight(true));
 
+  const bool merged = merged_wgrads(L);
+  // A graph captured from this call with merged weight gradients and more than one block crashed the runtime when
+  // it was instantiated (the single-block call, whose capture is a chain of plain forks and joins, replays fine):
+  // refused until the cause is known.
+  if (g_capturing && merged && nlayers > 1)
+    return fail(DOMINO_ERR_UNSUPPORTED, "streams[0] is being captured into a HIP graph: the backward of a stack of %d blocks with "
+                "p = %d > 2 row slices cannot be captured; capture one domino_layer_bwd call per block instead", nlayers, L.p);
   const StreamPlan S(streams, nstreams, L.p);
   const std::vector<char> used = S.used(true);
   TRY(fork_streams(S, used));
-  const bool merged = merged_wgrads(L);
   GradBufs gb[2] = {grad_bufs(L, workspace), grad_bufs(L, workspace)};
   if (merged && nlayers > 1) gb[1] = GradBufs{at(workspace, SL.d_pre2), at(workspace, SL.dx1_2), at(workspace, SL.dqkv2)};
   // merged weight gradients of the last block that used each set of gradient tensors: by matrix (down, up, qkv, out)
