@@ -44,7 +44,7 @@ def gemm_flops_per_launch(sc):
 
 def wgrad_rows(sc):
     """Rows one weight-gradient launch contracts over (the library's rule: merged over the slices when p > 2)."""
-    return sc.tokens if sc.p > 2 else sc.tokens // sc.p
+    return sc.tokens if sc.p > 2 and not sc.wgrad_per_slice else sc.tokens // sc.p
 
 
 def algorithmic_flops(sc):
@@ -195,6 +195,8 @@ def main():
     ap.add_argument("--graph", action="store_true", help="capture the step in a HIP graph and replay it")
     ap.add_argument("--p", type=int, default=None)
     ap.add_argument("--q", type=int, default=None)
+    ap.add_argument("--wgrad-per-slice", action="store_true",
+                    help="weight gradients slice by slice behind each input gradient (the order of Sec. 4.1.2) also for p > 2")
     ap.add_argument("--stack-layers", type=int, default=4,
                     help="with --layers 1: also time a stack of this many blocks (0 = skip) and report it under 'stack'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -218,6 +220,8 @@ def main():
     sc = synth.WORKLOADS[args.workload]
     if args.p or args.q:
         sc = sc.replace(p=args.p or sc.p, q=args.q or sc.q)
+    if args.wgrad_per_slice:
+        sc = sc.replace(wgrad_per_slice=1)
     if args.graph and not domino.domino_capture_supported(args.streams, sc.p):
         print("bench.py: --graph is limited to pools of 1, 2 or 4 streams (graph instantiation of the other pool "
               "sizes aborted inside the runtime on this ROCm; the library refuses to be captured with them)", file=sys.stderr)
@@ -360,7 +364,7 @@ def main():
             Cw = torch.zeros(Mw, Nw, device="cuda", dtype=torch.float32)
             torch.cuda.synchronize()
             run = lambda: domino.domino_gemm(domino.GEMM_TN, domino.EPI_ACC_F32, tile, A, Mw, B, Nw, Cw, Nw, Mw, Nw, Ms,
-                                             beta=0 if sc.p > 2 else 1, stream=s0)
+                                             beta=0 if Ms == sc.tokens else 1, stream=s0)
             run()
             tot_ms += timed(run, 10)
             tot_fl += 2.0 * Ms * Mw * Nw
@@ -406,7 +410,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": sc.name, "hidden": sc.hidden, "heads": sc.heads, "tp": sc.tp, "rank": sc.rank,
                    "batch": sc.batch, "seq": sc.seq, "ffn": sc.ffn, "p": sc.p, "q": sc.q,
-                   "arch": "llama" if sc.arch else "gpt", "streams": args.streams, "layers": args.layers},
+                   "arch": "llama" if sc.arch else "gpt", "streams": args.streams, "layers": args.layers,
+                   "weight_gradients": "slice by slice" if sc.p <= 2 or sc.wgrad_per_slice else "once per block over all rows"},
         "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS,
         "algorithmic_gflop_per_step": flops / 1e9, "ms_per_step_median": ms_median, "ms_per_step_min": ms_min,
         "ms_per_step_max": ms_max, "fwd_ms": fwd_ms, "bwd_ms": bwd_ms,

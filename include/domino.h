@@ -54,6 +54,9 @@ typedef struct domino_cfg {
   int32_t gelu_tanh;                   /* 1 = tanh form (default), 0 = erf form */
   float norm_eps;                      /* inside the square root; 1e-5 */
   float rope_base;                     /* 10000 */
+  int32_t wgrad_per_slice;             /* 0 (default): with p > 2 the weight gradients of a block are formed once over all
+                                          rows after the last slice's input gradients (see domino_layer_bwd);
+                                          1: always slice by slice behind each input gradient, as Sec. 4.1.2 orders them */
 } domino_cfg;
 
 /* Rank-local parameters.  h_l = hidden/tp, f_l = ffn/tp.
@@ -119,8 +122,8 @@ int domino_layer_fwd(const domino_cfg* cfg, const domino_params* params,
  *   dln2_others, dln1_others: [b,s,h] or NULL: the other ranks' sums of the two backward all-reduces.
  *   dln2_partial, dln1_partial: out [b,s,h]: this rank's input gradients of MLP-up and QKV.
  *   dx: out [b,s,h]; must not overlap dy.   grads: fp32; accumulate != 0 adds to their contents, else overwrites.
- * Weight gradients: with p <= 2 each slice adds its share right behind its input gradient, in slice order; with
- * p > 2 one launch per matrix contracts over all rows of the block after the last slice's input gradients (every
+ * Weight gradients: with p <= 2 (or cfg->wgrad_per_slice) each slice adds its share right behind its input gradient, in
+ * slice order; with p > 2 one launch per matrix contracts over all rows of the block after the last slice's input gradients (every
  * further slice would otherwise read and rewrite the whole fp32 gradient; on one GPU that traffic is time), the four
  * launches spread over the slices' streams.  Either way the order of the sums is fixed: results are run-to-run
  * identical and do not depend on the stream pool. */

@@ -73,6 +73,7 @@ constexpr long TWO_GIB = 1L << 31;
 struct Layout {
   int h, n, t, r, p, q, b, s, f, d, nl, hl, fl, upc, M, Ms, hq;
   bool llama;
+  bool merged;       // weight and vector gradients of a block in one launch each over all slices (see merged_wgrads)
   // saved block (bytes)
   size_t ln1, qkv, ctx, lse, x1, ln2, pre, act, mean1, rstd1, mean2, rstd2, saved_total;
   // workspace block (bytes)
@@ -104,6 +105,8 @@ int validate(const domino_cfg* c, Layout* L) {
   l.h = c->hidden; l.n = c->heads; l.t = c->tp; l.r = c->rank; l.p = c->p; l.q = c->q;
   l.b = c->batch; l.s = c->seq; l.f = c->ffn;
   l.llama = c->arch == DOMINO_ARCH_LLAMA;
+  if (c->wgrad_per_slice != 0 && c->wgrad_per_slice != 1) return fail(DOMINO_ERR_INVALID_ARG, "wgrad_per_slice must be 0 or 1");
+  l.merged = c->p > 2 && !c->wgrad_per_slice;
   l.d = l.h / l.n; l.nl = l.n / l.t; l.hl = l.nl * l.d; l.fl = l.f / l.t;
   l.upc = l.fl * (l.llama ? 2 : 1);
   l.hq = l.h / l.q;
@@ -524,7 +527,8 @@ GradBufs grad_bufs(const Layout& L, void* ws) { return {at(ws, L.d_pre), at(ws, 
 // p = 4) in launches a quarter as deep; the step sits on the board's power cap, so the saved traffic is saved time
 // (3.5-4.5 % of the step).  With one or two slices the slice-by-slice launches on second streams are faster (they fill
 // a chip that two slices leave half empty), so the rule follows p alone and the arithmetic does not depend on the pool.
-inline bool merged_wgrads(const Layout& L) { return L.p > 2; }
+// cfg->wgrad_per_slice keeps the slice-by-slice order of Sec. 4.1.2 for any p.
+inline bool merged_wgrads(const Layout& L) { return L.merged; }
 
 // out (+)= the partial rows that `nslices` consecutive slices, the first one's block of partial sums at `red`, left for
 // the eight vector gradients (norm gains and shifts, biases): one launch, slices and rows summed in index order

@@ -46,7 +46,8 @@ class DominoError(RuntimeError):
 
 class domino_cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("hidden", "heads", "tp", "rank", "p", "q", "batch", "seq", "ffn",
-                                         "arch", "gelu_tanh")] + [("norm_eps", C.c_float), ("rope_base", C.c_float)]
+                                         "arch", "gelu_tanh")] + [("norm_eps", C.c_float), ("rope_base", C.c_float),
+                                                                  ("wgrad_per_slice", C.c_int32)]
 
 
 class domino_params(C.Structure):
@@ -168,6 +169,7 @@ def make_cfg(sc=None, **kw) -> domino_cfg:
         for n in ("hidden", "heads", "tp", "rank", "p", "q", "batch", "seq", "ffn", "arch", "gelu_tanh",
                   "norm_eps", "rope_base"):
             vals[n] = getattr(sc, n)
+        vals["wgrad_per_slice"] = int(getattr(sc, "wgrad_per_slice", 0))
     vals.update(kw)
     vals.setdefault("gelu_tanh", 1)
     vals.setdefault("norm_eps", 1e-5)

@@ -52,6 +52,7 @@ class ShardConfig:
     norm_eps: float = 1e-5
     rope_base: float = 10000.0
     index: int = 0          # position in the workload table: offsets the seed
+    wgrad_per_slice: int = 0    # 1: weight gradients slice by slice also for p > 2 (the order of Sec. 4.1.2)
 
     @property
     def head_dim(self) -> int:

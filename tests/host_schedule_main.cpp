@@ -43,6 +43,7 @@ struct Op {
   bool vec_reduce = false;           // LAUNCH of the vector-gradient reduction
 };
 static std::vector<Op> g_ops;
+static bool g_merged = false;         // the configuration under test forms its weight gradients once per block
 static long g_rows = 0;              // rows (batch x sequence) of the configuration under test
 static bool g_capturing = false;
 static int g_failures = 0;
@@ -276,7 +277,7 @@ static void check_call(int first, hipStream_t s0, int p, bool capturing) {
   }
   for (auto& kv : per_matrix) {
     // slice by slice for one or two slices, one launch over all rows beyond that; either way every row exactly once
-    EXPECT((int)kv.second.size() == (p > 2 ? 1 : p), "%zu weight-gradient launches into one matrix for %d slices", kv.second.size(), p);
+    EXPECT((int)kv.second.size() == (g_merged ? 1 : p), "%zu weight-gradient launches into one matrix for %d slices", kv.second.size(), p);
     long rows = 0;
     for (int i : kv.second) rows += g_ops[i].regions[0].rows;
     EXPECT(rows == g_rows, "the weight-gradient launches into one matrix contract over %ld rows of %ld", rows, g_rows);
@@ -287,7 +288,7 @@ static void check_call(int first, hipStream_t s0, int p, bool capturing) {
       EXPECT(g_ops[kv.second[k]].regions[0].base > g_ops[kv.second[k - 1]].regions[0].base, "weight gradients into one matrix are not enqueued in slice order");
   }
   for (auto& kv : per_vector) {
-    EXPECT((int)kv.second.size() == (p > 2 ? 1 : p) || kv.second.empty(), "%zu vector-gradient reductions for %d slices", kv.second.size(), p);
+    EXPECT((int)kv.second.size() == (g_merged ? 1 : p) || kv.second.empty(), "%zu vector-gradient reductions for %d slices", kv.second.size(), p);
     long groups = 0;                 // every slice's partial rows exactly once (read off the launch's first vector, a norm gain)
     for (int i : kv.second) {
       const std::vector<Region>& r = g_ops[i].regions;
@@ -315,8 +316,9 @@ struct Buffers {                                    // addresses only: one arena
   }
 };
 
-static domino_cfg make_cfg(int arch, int p, int q) {
+static domino_cfg make_cfg(int arch, int p, int q, bool per_slice) {
   domino_cfg c{};
+  c.wgrad_per_slice = per_slice ? 1 : 0;
   c.hidden = 256; c.heads = 4; c.tp = 2; c.rank = 1; c.p = p; c.q = q; c.batch = 8; c.seq = 64;
   c.ffn = arch == DOMINO_ARCH_LLAMA ? 704 : 1024;
   c.arch = arch; c.gelu_tanh = 1; c.norm_eps = 1e-5f; c.rope_base = 10000.0f;
@@ -351,12 +353,13 @@ static Layer make_layer(Buffers& B, const domino_cfg& c) {
   return L;
 }
 
-static void run_case(int arch, int p, int q, int nstreams, bool capturing, int nlayers, bool parts) {
+static void run_case(int arch, int p, int q, int nstreams, bool capturing, int nlayers, bool parts, bool per_slice = false) {
   char name[160];
   std::snprintf(name, sizeof(name), "%s p=%d q=%d streams=%d%s layers=%d%s", arch ? "llama" : "gpt", p, q, nstreams,
-                capturing ? " capturing" : "", nlayers, parts ? " parts" : "");
+                capturing ? " capturing" : "", nlayers, parts ? (per_slice ? " parts per-slice" : " parts") : (per_slice ? " per-slice" : ""));
   g_case = name;
-  const domino_cfg c = make_cfg(arch, p, q);
+  const domino_cfg c = make_cfg(arch, p, q, per_slice);
+  g_merged = p > 2 && !per_slice;
   g_rows = (long)c.batch * c.seq;
   if (domino_validate_cfg(&c) != DOMINO_OK) { EXPECT(false, "configuration rejected: %s", domino_last_error()); return; }
   Buffers B((size_t)96 << 20);
@@ -424,7 +427,7 @@ static void run_case(int arch, int p, int q, int nstreams, bool capturing, int n
     if (!capturing) check_call(first, s0, p, false);
     const int mid = (int)g_ops.size();
     const int rc = domino_stack_bwd(&c, nlayers, P.data(), dy, bio.data(), dx, G.data(), 0, ws, wsb, streams.data(), nstreams);
-    if (capturing && p > 2 && nlayers > 1) {      // merged weight gradients over several blocks: not under capture
+    if (capturing && g_merged && nlayers > 1) {   // merged weight gradients over several blocks: not under capture
       EXPECT(rc == DOMINO_ERR_UNSUPPORTED, "a captured stack backward with merged weight gradients returned %d", rc);
       EXPECT((int)g_ops.size() == mid, "a refused call enqueued %zu operations", g_ops.size() - mid);
       check_call(first, s0, p, true);             // the captured forward on its own
@@ -447,6 +450,12 @@ int main() {
           // four blocks: the tensors handed from block to block, taken in turn, come round again
           if (q == 2) { run_case(arch, p, q, ns, false, 4, false); run_case(arch, p, q, ns, true, 4, false); cases += 2; }
           if (q == 1) { run_case(arch, p, q, ns, false, 1, true); ++cases; }
+          if (p > 2 && q == 2) {      // the slice-by-slice weight gradients of Sec. 4.1.2 for more than two slices
+            run_case(arch, p, q, ns, false, 1, false, true); run_case(arch, p, q, ns, true, 1, false, true);
+            run_case(arch, p, q, ns, false, 4, false, true); run_case(arch, p, q, ns, true, 4, false, true);
+            cases += 4;
+          }
+          if (p == 4 && q == 1) { run_case(arch, p, q, ns, false, 1, true, true); ++cases; }
         }
   // the check must be able to fail: two launches on different fake streams that write one buffer, no event between them
   {

@@ -97,7 +97,7 @@ _ORACLE_CACHE = {}     # the last workload's inputs and oracle result: it does n
 def case(H, sc, random_affine=False, with_others=True, nstreams=4):
     """One forward + backward through the C ABI against the oracle.  The oracle result depends on the shard, not on
     the slicing, so consecutive cases that differ in (p, q, streams) only share one oracle run."""
-    key = (sc.replace(p=1, q=1), random_affine, with_others)
+    key = (sc.replace(p=1, q=1, wgrad_per_slice=0), random_affine, with_others)
     if key not in _ORACLE_CACHE:
         _ORACLE_CACHE.clear()
         params = synth.make_rank_params(sc, random_affine=random_affine)
@@ -119,6 +119,15 @@ TINYL = synth.WORKLOADS["tiny-llama"]
 def test_tiny_every_slicing(H, base, p, q):
     sc = base.replace(p=p, q=q, batch=p if p >= 4 else base.batch)
     case(H, sc, random_affine=True)
+
+
+@pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
+@pytest.mark.parametrize("p,q,nstreams", [(4, 2, 4), (4, 1, 2), (8, 2, 4), (4, 4, 8)])
+def test_tiny_weight_gradients_slice_by_slice_for_more_than_two_slices(H, base, p, q, nstreams):
+    """cfg.wgrad_per_slice: the order of Sec. 4.1.2 (a slice's weight gradient right behind its input gradient, summed
+    over the slices in slice order) instead of one launch per matrix over all rows."""
+    sc = base.replace(p=p, q=q, batch=p, wgrad_per_slice=1)
+    case(H, sc, random_affine=True, nstreams=nstreams)
 
 
 @pytest.mark.parametrize("base", [TINY, TINYL], ids=["gpt", "llama"])
@@ -214,6 +223,11 @@ def test_full_size_shard_at_other_slicings(H, name, p, q, nstreams):
     case(H, synth.WORKLOADS[name].replace(p=p, q=q), random_affine=True, nstreams=nstreams)
 
 
+def test_full_size_shard_with_weight_gradients_slice_by_slice(H):
+    """The benchmark's shard as configured (p=4, q=2, 4 streams) in the order of Sec. 4.1.2 (cfg.wgrad_per_slice)."""
+    case(H, synth.WORKLOADS["gpt3-13b"].replace(wgrad_per_slice=1), random_affine=True, nstreams=4)
+
+
 def test_schedule_invariance_bitwise(H):
     """The same call on 1 stream and on 4 streams: identical bits (accumulation order is fixed)."""
     sc = TINY.replace(batch=4, p=4, q=2)
@@ -223,6 +237,17 @@ def test_schedule_invariance_bitwise(H):
     a = run_gpu(H, sc, params, x, dy, others, nstreams=1)
     b = run_gpu(H, sc, params, x, dy, others, nstreams=4)
     c = run_gpu(H, sc, params, x, dy, others, nstreams=8)
+    _same_bits(a, b, c)
+    # ... and so does the slice-by-slice order of the weight gradients (its sums differ from the merged ones in rounding only)
+    ps = sc.replace(wgrad_per_slice=1)
+    a2 = run_gpu(H, ps, params, x, dy, others, nstreams=1)
+    _same_bits(a2, run_gpu(H, ps, params, x, dy, others, nstreams=4), run_gpu(H, ps, params, x, dy, others, nstreams=8))
+    for k, g in a["grads"].items():
+        if g is not None:
+            np.testing.assert_allclose(a2["grads"][k], g, rtol=0, atol=1e-5 * float(np.abs(g).max()), err_msg=k)
+
+
+def _same_bits(a, b, c):
     for k in ("attn_partial", "mlp_partial", "y", "dln2_partial", "dln1_partial", "dx"):
         np.testing.assert_array_equal(a[k], b[k], err_msg=k)
         np.testing.assert_array_equal(a[k], c[k], err_msg=k)
@@ -346,14 +371,17 @@ def test_two_host_threads_with_their_own_pools(H):
                 np.testing.assert_array_equal(g.cpu().numpy(), ref["grads"][k], err_msg=k)
 
 
+@pytest.mark.parametrize("per_slice", [0, 1], ids=["", "wgrads-slice-by-slice"])
 @pytest.mark.parametrize("p,nstreams", [(4, 4), (2, 4), (1, 2), (2, 2), (4, 1)],
                          ids=["4slices-4streams", "2slices-4streams", "1slice-2streams", "2slices-2streams", "4slices-1stream"])
-def test_graph_replay_is_bitwise_the_eager_step(H, p, nstreams):
+def test_graph_replay_is_bitwise_the_eager_step(H, p, nstreams, per_slice):
     """The step captured once in a HIP graph on streams[0] (the library forks and joins the pool inside the capture,
     allocates nothing and records no memset) and replayed several times, with eager steps and synchronisations in
     between: every replay leaves the bits of the eager step.  (With twice as many streams as slices an eager backward
     runs the weight gradients on streams of their own; a captured one keeps them on the slices' streams.)"""
-    sc = TINY.replace(batch=4, p=p, q=2)
+    if per_slice and p <= 2:
+        pytest.skip("cfg.wgrad_per_slice changes nothing for one or two slices")
+    sc = TINY.replace(batch=4, p=p, q=2, wgrad_per_slice=per_slice)
     params = synth.make_rank_params(sc, random_affine=True)
     x, dy = synth.make_activations(sc)
     others = synth.make_others(sc)

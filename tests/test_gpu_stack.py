@@ -69,8 +69,17 @@ def run_layer_by_layer(H, sc, params, others, x, dy, nstreams):
     # block on the tensors those launches read, kept twice and used in turn, come round again
     ("tiny", 5, 4, 2, 4), ("tiny-llama", 4, 4, 2, 4), ("tiny", 4, 4, 1, 3), ("tiny", 3, 4, 2, 1)])
 def test_stack_is_bitwise_the_blocks_called_one_by_one(H, base, nlayers, p, q, nstreams):
+    stack_against_single_blocks(H, synth.WORKLOADS[base].replace(p=p, q=q, batch=4), nlayers, nstreams)
+
+
+@pytest.mark.parametrize("base", ["tiny", "tiny-llama"])
+def test_stack_with_weight_gradients_slice_by_slice(H, base):
+    """cfg.wgrad_per_slice with four slices over four blocks: slices run on from block to block without meeting."""
+    stack_against_single_blocks(H, synth.WORKLOADS[base].replace(p=4, q=2, batch=4, wgrad_per_slice=1), 4, 4)
+
+
+def stack_against_single_blocks(H, sc, nlayers, nstreams):
     from paper_2409_15241_amd import domino
-    sc = synth.WORKLOADS[base].replace(p=p, q=q, batch=4)
     params, others = synth.make_stack(sc, nlayers, random_affine=True)
     x, dy = synth.make_activations(sc)
     st = run_stack(H, sc, params, others, x, dy, nstreams)
@@ -191,11 +200,12 @@ def test_full_size_stack_matches_single_blocks_bitwise(H, name):
                "blocks crashed inside the runtime and the cause has not been shown from the host side: the library refuses "
                "such captures (test_capture_of_a_deep_stack_backward_with_merged_weight_gradients_is_refused) and the case "
                "stays off the GPU")),
-    ("tiny-llama", 2)])
+    ("tiny-llama", 2), ("tiny-per-slice", 4)])
 def test_captured_stack_replays_bitwise(H, base, p):
     """A stack of three blocks captured in a HIP graph on streams[0] (pool of 4) and replayed three times with eager
-    work in between: every replay leaves the bits of the eager stack."""
-    sc = synth.WORKLOADS[base].replace(p=p, q=2, batch=4)
+    work in between: every replay leaves the bits of the eager stack.  (Four slices: with cfg.wgrad_per_slice.)"""
+    per_slice = base.endswith("-per-slice")
+    sc = synth.WORKLOADS[base.replace("-per-slice", "")].replace(p=p, q=2, batch=4, wgrad_per_slice=int(per_slice))
     nlayers = 3
     params, others = synth.make_stack(sc, nlayers, random_affine=True)
     x, dy = synth.make_activations(sc)
