@@ -43,6 +43,7 @@ def cfg(**kw):
     (dict(tp=3), domino.ERR_INDIVISIBLE),            # heads 4 % 3
     (dict(ffn=1001), domino.ERR_INDIVISIBLE),        # ffn % tp
     (dict(heads=3), domino.ERR_INDIVISIBLE),         # hidden % heads
+    (dict(wgrad_per_slice=2), domino.ERR_INVALID_ARG),   # a switch: 0 or 1
     (dict(rank=2), domino.ERR_INVALID_ARG),
     (dict(rank=-1), domino.ERR_INVALID_ARG),
     (dict(batch=0), domino.ERR_INVALID_ARG),
