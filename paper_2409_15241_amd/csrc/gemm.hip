@@ -413,11 +413,14 @@ int gemm_pick_tile(int M, int N, int concurrency) {
     const double tiles = (double)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
     double rounds, rate = c.rate;
     if (concurrency >= 3) {
-      // a launch of very few tiles is a long serial kernel on its stream's critical path: charge a
-      // tile shape for leaving most of a quarter of its fair share of the chip (256 / concurrency CUs)
-      // unused.  (Charging it against the whole share was measured 0.7 % slower on the 13B shard: the
-      // 640-column input gradient is best served by 24 tiles of 256x256, padding included.)
-      const double share = 64.0 / concurrency;
+      // a launch of few tiles is a long serial kernel on its stream's critical path, and the other
+      // launches in flight do not always fill the chip beside it: charge a tile shape for leaving more
+      // than three eighths of its fair share of the chip (256 / concurrency CUs) unused.  Measured on
+      // the 640-column input gradient of the 13B shard, four such launches side by side: 24 tiles of
+      // 256x256 take 103 us, 40 tiles of 256x128 79 us (0.5 % of the step).  (While the slices' weight
+      // gradients still ran between their input gradients, charging against a quarter of the share was
+      // the better rule; charging against the whole share was 0.7 % slower then.)
+      const double share = 160.0 / concurrency;
       rounds = tiles / 256.0 * (tiles < share ? share / tiles : 1.0);
     } else if (c.id == GEMM_TILE_128x128) {
       const double t = tiles * concurrency;
